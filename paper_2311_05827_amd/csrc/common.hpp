@@ -1,0 +1,170 @@
+// Internal declarations shared by the HIP translation units of libaccept (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "accept.h"
+
+namespace accept {
+
+constexpr int kBlock = 256;       // threads per workgroup: 4 wavefronts of 64
+constexpr int kWave = 64;
+constexpr int kTileElems = 8192;  // elements one workgroup quantizes and packs per iteration
+
+struct bf16_t {
+  uint16_t bits;
+};
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr int VEC = 4;  // elements per 16-byte vector
+};
+template <>
+struct Elem<bf16_t> {
+  static constexpr int VEC = 8;
+};
+
+// ---- event bracketing for the *_timed entry points -------------------------------------
+struct StageTimer {
+  hipEvent_t ev[ACCEPT_MAX_STAGES + 1];
+  int n = 0;
+  bool failed = false;
+  void mark(hipStream_t s) {
+    if (n > ACCEPT_MAX_STAGES) return;
+    if (hipEventCreate(&ev[n]) != hipSuccess) { failed = true; return; }
+    if (hipEventRecord(ev[n], s) != hipSuccess) failed = true;
+    ++n;
+  }
+};
+inline void mark(StageTimer* t, hipStream_t s) {
+  if (t) t->mark(s);
+}
+
+// ---- scheme U (uniform) -----------------------------------------------------------------
+enum UMode { U_TENSOR = 0, U_SEGMENTED = 1, U_GENERIC = 2 };
+
+struct UPlan {
+  int mode;
+  int vec;             // elements per 16-byte vector of the input type
+  int64_t N, m, C, seg_len;
+  int range_grid;      // U_TENSOR: workgroups of the range kernel = number of partial maxima
+  int64_t cps;         // U_SEGMENTED: chunks per segment
+  int64_t chunk_vecs;  // U_SEGMENTED: 16-byte vectors per chunk
+  int64_t items;       // U_SEGMENTED: n*C*cps partial maxima
+  bool fast;           // vector path usable (every 16-byte vector lies inside one range group)
+  size_t off_rtab;     // byte offset of the per-channel reciprocal table in the workspace
+  size_t bytes;        // workspace bytes
+};
+
+UPlan make_uplan(const accept_desc& d);
+
+hipError_t launch_uniform_compress(const accept_desc& d, const UPlan& p, const void* x, void* header,
+                                   void* payload, void* ws, hipStream_t s, StageTimer* tm);
+hipError_t launch_uniform_decompress(const accept_desc& d, const void* header, const void* payload,
+                                     void* xhat, hipStream_t s, StageTimer* tm);
+
+// ---- scheme M (multi-bit) ---------------------------------------------------------------
+struct MPlan {
+  int vec;          // columns per work item: 16-byte vectors when rows stay 16-byte aligned, else 1
+  int64_t G;        // ceil(n/8) row groups
+  int64_t items;    // G * (m / vec)
+  int grid;         // workgroups of the encode kernel = number of partial-sum records
+  int nstat;        // doubles per record
+  size_t bytes;
+};
+
+MPlan make_mplan(const accept_desc& d);
+
+hipError_t launch_mbq_compress(const accept_desc& d, const MPlan& p, const void* x, const float* alpha_prev,
+                               void* header, void* payload, void* ws, hipStream_t s, StageTimer* tm);
+hipError_t launch_mbq_decompress(const accept_desc& d, const void* header, const void* payload, void* xhat,
+                                 hipStream_t s, StageTimer* tm);
+hipError_t launch_mbq_init(const accept_desc& d, const MPlan& p, const void* x, float* alpha0, void* ws,
+                           hipStream_t s);
+
+// ---- device helpers ---------------------------------------------------------------------
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ float u32_as_f32(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t f32_as_u32(float f) { return __float_as_uint(f); }
+
+// 16-byte vector load widened to float32.
+__device__ __forceinline__ void load_vec(const float* p, float (&f)[4]) {
+  const float4 v = *reinterpret_cast<const float4*>(p);
+  f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+}
+__device__ __forceinline__ void load_vec(const bf16_t* p, float (&f)[8]) {
+  const uint4 v = *reinterpret_cast<const uint4*>(p);
+  f[0] = u32_as_f32(v.x << 16); f[1] = u32_as_f32(v.x & 0xFFFF0000u);
+  f[2] = u32_as_f32(v.y << 16); f[3] = u32_as_f32(v.y & 0xFFFF0000u);
+  f[4] = u32_as_f32(v.z << 16); f[5] = u32_as_f32(v.z & 0xFFFF0000u);
+  f[6] = u32_as_f32(v.w << 16); f[7] = u32_as_f32(v.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ float load_one(const float* p) { return *p; }
+__device__ __forceinline__ float load_one(const bf16_t* p) { return u32_as_f32(uint32_t(p->bits) << 16); }
+
+// float32 -> bfloat16 bits, round to nearest even (finite values).
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+  const uint32_t b = f32_as_u32(f);
+  return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ void store_vec(float* p, const float (&f)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
+}
+__device__ __forceinline__ void store_vec(bf16_t* p, const float (&f)[8]) {
+  uint4 v;
+  v.x = bf16_rne(f[0]) | (bf16_rne(f[1]) << 16);
+  v.y = bf16_rne(f[2]) | (bf16_rne(f[3]) << 16);
+  v.z = bf16_rne(f[4]) | (bf16_rne(f[5]) << 16);
+  v.w = bf16_rne(f[6]) | (bf16_rne(f[7]) << 16);
+  *reinterpret_cast<uint4*>(p) = v;
+}
+__device__ __forceinline__ void store_one(float* p, float f) { *p = f; }
+__device__ __forceinline__ void store_one(bf16_t* p, float f) { p->bits = uint16_t(bf16_rne(f)); }
+
+// Lane exchange inside a row of 16 lanes with a DPP control word (all lanes stay valid).
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return uint32_t(__builtin_amdgcn_update_dpp(int(v), int(v), CTRL, 0xF, 0xF, false));
+}
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+// Maximum over the 64 lanes of a wavefront; every lane receives the result.  Operands are
+// non-negative floats, compared through their bit patterns' float view.
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, u32_as_f32(dpp_u32<kDppQuadSwap1>(f32_as_u32(v))));
+  v = fmaxf(v, u32_as_f32(dpp_u32<kDppQuadSwap2>(f32_as_u32(v))));
+  v = fmaxf(v, u32_as_f32(dpp_u32<kDppRowHalfMirror>(f32_as_u32(v))));
+  v = fmaxf(v, u32_as_f32(dpp_u32<kDppRowMirror>(f32_as_u32(v))));
+  v = fmaxf(v, __shfl_xor(v, 16, kWave));
+  v = fmaxf(v, __shfl_xor(v, 32, kWave));
+  return v;
+}
+
+// Sum over the 64 lanes in a fixed butterfly order (deterministic); all lanes get the sum.
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// u in [0,1) on a 2^-24 grid: top 24 bits of splitmix64's output function at
+// seed + (idx+1) * 0x9E3779B97F4A7C15.
+__device__ __forceinline__ float counter_uniform(uint64_t seed, uint64_t idx) {
+  uint64_t z = seed + (idx + 1ull) * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z = z ^ (z >> 31);
+  return float(uint32_t(z >> 40)) * 0x1p-24f;
+}
+
+#endif  // __HIPCC__
+
+}  // namespace accept

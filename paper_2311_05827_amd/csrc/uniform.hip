@@ -1,0 +1,617 @@
+// Scheme U on gfx950: max-abs range reduction, fused quantize + dense bit pack, fused
+// unpack + dequantize (paper paragraphs "Backward Quantizer", "Backward Encoder",
+// "Backward Decoder", "Backward Dequantizer"; generalised from k in {4, 8} to k in 2..8
+// and to per-channel ranges).
+//
+// Data movement design: all tensor traffic is 16-byte vector loads/stores that are
+// contiguous across the 64 lanes of a wavefront.  The only cross-lane exchange in the
+// compressor is one LDS round trip of already-quantized 4-code "pieces" (4k bits each):
+// 8 pieces = 32 codes = exactly k dwords for every k, so one lane can emit whole dwords and
+// no global atomics are needed even when codes straddle dword boundaries.
+#include "common.hpp"
+
+namespace accept {
+
+namespace {
+
+constexpr float kTinyRange = 0x1p-100f;     // smaller ranges count as an all-zero tensor
+constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to integer, half to even
+constexpr int kRangeGridMax = 1024;         // partial maxima of the per-tensor range pass
+constexpr int kQuantGridMax = 2048;         // workgroups of the quantize+pack kernel
+constexpr int kDequantGridMax = 8192;
+
+// s = c / L and r = L / c as correctly rounded float32 quotients (a float64 quotient of two
+// float32 values rounds to the same float32 as the exact quotient).
+__device__ __forceinline__ void scale_from_range(float c, int k, float& s, float& r) {
+  const double L = double((1 << (k - 1)) - 1);
+  if (c >= kTinyRange) {
+    s = float(double(c) / L);
+    r = float(L / double(c));
+  } else {
+    s = 0.0f;
+    r = 0.0f;
+  }
+}
+
+// Position of a 16-byte vector inside the channel structure, advanced without divisions.
+struct ChanPos {
+  int64_t rem;  // vector offset inside the current segment, < seg_vecs
+  int32_t ch;   // channel of the current segment, < C
+};
+struct ChanStep {
+  int64_t dr;   // step mod seg_vecs
+  int32_t dch;  // (step / seg_vecs) mod C
+};
+struct ChanGeom {
+  int64_t seg_vecs;  // vectors per segment (segment = one channel of one batch row)
+  int32_t C;
+  ChanStep s256;     // step of 256 vectors
+  ChanStep sgrid;    // step of one grid stride (gridDim.x tiles, or gridDim.x*256 vectors)
+};
+__device__ __forceinline__ ChanPos chan_init(const ChanGeom& g, int64_t vec_index) {
+  ChanPos p;
+  const int64_t seg = vec_index / g.seg_vecs;
+  p.rem = vec_index - seg * g.seg_vecs;
+  p.ch = int32_t(seg % g.C);
+  return p;
+}
+__device__ __forceinline__ void chan_advance(const ChanGeom& g, ChanPos& p, const ChanStep& st) {
+  p.rem += st.dr;
+  int32_t carry = 0;
+  if (p.rem >= g.seg_vecs) { p.rem -= g.seg_vecs; carry = 1; }
+  p.ch += st.dch + carry;
+  if (p.ch >= g.C) p.ch -= g.C;
+}
+
+// =========================================================================== range (U1)
+// One range for the tensor: grid-stride 16-byte loads, DPP wave reduction, one partial
+// maximum per workgroup.  max is exact and order independent, so the result is
+// reproducible without atomics or a fixed order.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void range_tensor_kernel(const T* __restrict__ x, int64_t N,
+                                                               float* __restrict__ partials) {
+  constexpr int VEC = Elem<T>::VEC;
+  constexpr int UNROLL = 4;
+  __shared__ float red[kBlock / kWave];
+  const int64_t nvec = N / VEC;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  float c = 0.0f;
+  int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  for (; v + (UNROLL - 1) * stride < nvec; v += UNROLL * stride) {
+    float f[UNROLL][VEC];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) load_vec(x + (v + u * stride) * VEC, f[u]);
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[u][e]));
+  }
+  for (; v < nvec; v += stride) {
+    float f[VEC];
+    load_vec(x + v * VEC, f);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[e]));
+  }
+  if (blockIdx.x == 0 && int64_t(threadIdx.x) < N - nvec * VEC)
+    c = fmaxf(c, fabsf(load_one(x + nvec * VEC + threadIdx.x)));
+  c = wave_max(c);
+  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float b = red[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / kWave; ++w) b = fmaxf(b, red[w]);
+    partials[blockIdx.x] = b;
+  }
+}
+
+// One range per channel, long segments: one wavefront reduces one chunk of one segment
+// (segment = channel ch of batch row r, contiguous in memory); partial index =
+// (r*C + ch)*cps + chunk.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restrict__ x, int64_t items, int64_t cps,
+                                                                 int64_t seg_vecs, int64_t chunk_vecs,
+                                                                 float* __restrict__ partials) {
+  constexpr int VEC = Elem<T>::VEC;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t waves = int64_t(gridDim.x) * (kBlock / kWave);
+  for (int64_t it = int64_t(blockIdx.x) * (kBlock / kWave) + threadIdx.x / kWave; it < items; it += waves) {
+    const int64_t sid = it / cps;
+    const int64_t chunk = it - sid * cps;
+    const int64_t first = chunk * chunk_vecs;
+    int64_t count = seg_vecs - first;
+    if (count > chunk_vecs) count = chunk_vecs;
+    const T* base = x + (sid * seg_vecs + first) * VEC;
+    float c = 0.0f;
+    int64_t j = lane;
+    for (; j + 3 * kWave < count; j += 4 * kWave) {
+      float f[4][VEC];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) load_vec(base + (j + u * kWave) * VEC, f[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[u][e]));
+    }
+    for (; j < count; j += kWave) {
+      float f[VEC];
+      load_vec(base + j * VEC, f);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[e]));
+    }
+    c = wave_max(c);  // every lane of the wavefront reaches this point: the loop bounds are wave-uniform
+    if (lane == 0) partials[it] = c;
+  }
+}
+
+// Any channel geometry: one atomic max per element on the channel's slot (bit patterns of
+// non-negative floats order like unsigned integers).  Slow; correctness path only.
+__global__ void zero_u32_kernel(uint32_t* p, int64_t count) {
+  for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < count; i += int64_t(gridDim.x) * blockDim.x)
+    p[i] = 0u;
+}
+template <typename T>
+__global__ __launch_bounds__(kBlock) void range_generic_kernel(const T* __restrict__ x, int64_t N, int64_t m,
+                                                                int64_t seg_len, uint32_t* __restrict__ chanmax) {
+  for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < N; i += int64_t(gridDim.x) * kBlock) {
+    const int64_t ch = (i % m) / seg_len;
+    atomicMax(chanmax + ch, f32_as_u32(fabsf(load_one(x + i))));
+  }
+}
+
+// U1b per channel: reduce the channel's partial maxima, write s to the header and the
+// reciprocal r to the workspace table.  One wavefront per channel.
+__global__ __launch_bounds__(kWave) void range_finalize_kernel(const float* __restrict__ partials, int64_t n_rows,
+                                                                int64_t C, int64_t cps, int k,
+                                                                float* __restrict__ header, float* __restrict__ rtab) {
+  const int64_t ch = blockIdx.x;
+  float c = 0.0f;
+  const int64_t per = n_rows * cps;
+  for (int64_t j = threadIdx.x; j < per; j += kWave) {
+    const int64_t r = j / cps;
+    const int64_t q = j - r * cps;
+    c = fmaxf(c, partials[(r * C + ch) * cps + q]);
+  }
+  c = wave_max(c);
+  if (threadIdx.x == 0) {
+    float s, r;
+    scale_from_range(c, k, s, r);
+    header[ch] = s;
+    rtab[ch] = r;
+  }
+}
+
+// =========================================================================== quantize (U2)
+// One element: v = x * r (one float32 multiply), round, clamp, offset to a k-bit code.
+template <int K, bool STOCH>
+__device__ __forceinline__ uint32_t quantize1(float f, float r, uint64_t seed, int64_t idx) {
+  constexpr int HALF = 1 << (K - 1);
+  constexpr uint32_t MASK = (1u << K) - 1u;
+  const float v = __fmul_rn(f, r);
+  if (!STOCH) {
+    // Round half to even through the magic-number add.  |v| <= L(1 + 2^-23), so the rounded
+    // value lies in [-L, L] and the clamp of the definition never binds; the mask only keeps
+    // codes of non-finite inputs inside their k bits.  The sum's low mantissa bits are
+    // q + HALF (k < 8) or q mod 256 (k = 8).
+    const float t = __fadd_rn(v, kRoundMagic + float(K == 8 ? 0 : HALF));
+    return f32_as_u32(t) & MASK;
+  }
+  const float fl = floorf(v);
+  const float pr = __fsub_rn(v, fl);  // exact
+  const float u = counter_uniform(seed, uint64_t(idx));
+  int q = int(fl) + (u < pr ? 1 : 0);
+  q = min(max(q, -HALF), HALF - 1);
+  return (K == 8) ? (uint32_t(q) & 0xFFu) : uint32_t(q + HALF);
+}
+
+// Four consecutive elements -> one 4k-bit piece, first element most significant.
+template <int K, bool STOCH>
+__device__ __forceinline__ uint32_t quantize4(const float* f, float r, uint64_t seed, int64_t idx0) {
+  uint32_t piece = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) piece = (piece << K) | quantize1<K, STOCH>(f[e], r, seed, idx0 + e);
+  return piece;
+}
+
+// U3 for 32 consecutive codes: eight 4k-bit pieces -> k dwords of the big-endian bit
+// stream, each dword byte-swapped into memory order.
+template <int K>
+__device__ __forceinline__ void pack8(const uint32_t (&P)[8], uint32_t (&out)[K]) {
+  constexpr int W = 4 * K;
+  uint64_t acc = 0;
+  int nb = 0, o = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    acc = (W == 32) ? ((acc << 32) | P[i]) : ((acc << W) | P[i]);
+    nb += W;
+    if (nb >= 32) {
+      out[o++] = __builtin_bswap32(uint32_t(acc >> (nb - 32)));
+      nb -= 32;
+    }
+  }
+}
+
+template <int K>
+struct alignas((K % 4 == 0) ? 16 : (K % 2 == 0) ? 8 : 4) Dwords {
+  uint32_t v[K];
+};
+
+// Slow path for one group of 8 elements -> k bytes (tails and odd channel geometries):
+// scalar loads, per-byte stores guarded by the payload size.  Elements at or beyond N
+// contribute zero bits.
+template <typename T, int K, bool STOCH, typename RFn>
+__device__ __forceinline__ void quantize_group8(const T* __restrict__ x, uint8_t* __restrict__ payload, int64_t grp,
+                                                int64_t N, int64_t payload_bytes, uint64_t seed, RFn r_of) {
+  uint64_t acc = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int64_t i = grp * 8 + e;
+    uint64_t code = 0;
+    if (i < N) code = quantize1<K, STOCH>(load_one(x + i), r_of(i), seed, i);
+    acc = (acc << K) | code;
+  }
+#pragma unroll
+  for (int b = 0; b < K; ++b) {
+    const int64_t byte = grp * K + b;
+    if (byte < payload_bytes) payload[byte] = uint8_t(acc >> (8 * (K - 1 - b)));
+  }
+}
+
+// Fused U2 + U3.  Per iteration a workgroup takes one tile of 8192 consecutive elements:
+// every thread loads 16-byte vectors (contiguous across lanes), quantizes them into pieces,
+// parks the pieces in LDS; after one barrier thread g reads pieces 8g..8g+7 (32 consecutive
+// elements) and emits k contiguous dwords.  The piece buffer is double buffered so that one
+// barrier per tile is enough.  Per-tensor mode folds U1b into the prologue: every workgroup
+// reduces the range pass's partial maxima itself and workgroup 0 writes s to the header.
+template <typename T, int K, bool PERCH, bool STOCH>
+__global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
+    const T* __restrict__ x, uint32_t* __restrict__ payload32, float* __restrict__ header,
+    const float* __restrict__ partials, int npart, const float* __restrict__ rtab, int64_t N, int64_t full_tiles,
+    int64_t slow_first_group, int64_t payload_bytes, ChanGeom geom, int64_t m, int64_t seg_len, uint64_t seed) {
+  constexpr int VEC = Elem<T>::VEC;
+  constexpr int QPV = VEC / 4;                       // pieces per vector
+  constexpr int LOADS = kTileElems / (kBlock * VEC);  // vectors per thread per tile
+  constexpr int PIECES = kTileElems / 4;
+  __shared__ __attribute__((aligned(16))) uint32_t pieces[2][PIECES];
+  __shared__ float red[kBlock / kWave];
+
+  const int tid = threadIdx.x;
+  float r_tensor = 0.0f;
+  if (!PERCH) {
+    float c = 0.0f;
+    for (int i = tid; i < npart; i += kBlock) c = fmaxf(c, partials[i]);
+    c = wave_max(c);
+    if ((tid & (kWave - 1)) == 0) red[tid / kWave] = c;
+    __syncthreads();
+    c = red[0];
+#pragma unroll
+    for (int w = 1; w < kBlock / kWave; ++w) c = fmaxf(c, red[w]);
+    float s;
+    scale_from_range(c, K, s, r_tensor);
+    if (blockIdx.x == 0 && tid == 0) header[0] = s;
+  }
+
+  ChanPos tile_pos{0, 0};
+  if (PERCH && full_tiles > 0)
+    tile_pos = chan_init(geom, int64_t(blockIdx.x) * (kTileElems / VEC) + tid);
+
+  int buf = 0;
+  for (int64_t tile = blockIdx.x; tile < full_tiles; tile += gridDim.x, buf ^= 1) {
+    const T* xt = x + tile * kTileElems;
+    float f[LOADS][VEC];
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) load_vec(xt + (u * kBlock + tid) * VEC, f[u]);
+    ChanPos pos = tile_pos;
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) {
+      float r = r_tensor;
+      if (PERCH) {
+        r = rtab[pos.ch];
+        chan_advance(geom, pos, geom.s256);
+      }
+      const int64_t e0 = tile * kTileElems + int64_t(u * kBlock + tid) * VEC;
+#pragma unroll
+      for (int h = 0; h < QPV; ++h)
+        pieces[buf][(u * kBlock + tid) * QPV + h] = quantize4<K, STOCH>(&f[u][4 * h], r, seed, e0 + 4 * h);
+    }
+    if (PERCH) chan_advance(geom, tile_pos, geom.sgrid);
+    __syncthreads();
+    const uint4 a = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid]);
+    const uint4 b = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid + 4]);
+    const uint32_t P[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    Dwords<K> out;
+    pack8<K>(P, out.v);
+    *reinterpret_cast<Dwords<K>*>(payload32 + (tile * kBlock + tid) * K) = out;
+  }
+
+  // Everything the tile loop did not cover, 8 elements (k bytes) per thread.
+  const int64_t groups = (N + 7) / 8;
+  uint8_t* payload8 = reinterpret_cast<uint8_t*>(payload32);
+  for (int64_t g = slow_first_group + int64_t(blockIdx.x) * kBlock + tid; g < groups;
+       g += int64_t(gridDim.x) * kBlock) {
+    if (PERCH) {
+      quantize_group8<T, K, STOCH>(x, payload8, g, N, payload_bytes, seed,
+                                   [&](int64_t i) { return rtab[(i % m) / seg_len]; });
+    } else {
+      quantize_group8<T, K, STOCH>(x, payload8, g, N, payload_bytes, seed, [&](int64_t) { return r_tensor; });
+    }
+  }
+}
+
+// ====================================================================== dequantize (U4+U5)
+// Four consecutive codes starting at element index e0 (a multiple of 4): load the one or two
+// payload dwords that hold their 4k bits, view them as a big-endian 64-bit window, extract,
+// remove the offset by sign extension, multiply by s.
+template <int K>
+__device__ __forceinline__ void dequant4(const uint32_t* __restrict__ payload32, int64_t e0, float s, float* out) {
+  constexpr int W = 4 * K;
+  const int64_t bit = e0 * K;
+  const int64_t w0 = bit >> 5;
+  const int sh = int(bit & 31);
+  const uint32_t hi = __builtin_bswap32(payload32[w0]);
+  uint32_t lo = 0;
+  if ((32 % W != 0) && sh + W > 32) lo = __builtin_bswap32(payload32[w0 + 1]);
+  const uint64_t win = (uint64_t(hi) << 32) | lo;
+  uint32_t piece = uint32_t(win >> (64 - W - sh));
+  // Offset binary -> two's complement: flip the top bit of each k-bit field (k < 8).
+  if (K < 8) {
+    constexpr uint32_t TOP = (1u << (K - 1)) * ((1u) | (1u << K) | (1u << (2 * K)) | (1u << (3 * K)));
+    piece ^= TOP;
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int q = __builtin_amdgcn_sbfe(int(piece), K * (3 - e), K);
+    out[e] = __fmul_rn(float(q), s);
+  }
+}
+
+// Slow path: one element, byte loads guarded by the payload size.
+template <int K>
+__device__ __forceinline__ float dequant1(const uint8_t* __restrict__ payload, int64_t i, int64_t payload_bytes,
+                                          float s) {
+  const int64_t bit = i * K;
+  const int64_t b0 = bit >> 3;
+  const int sh = int(bit & 7);
+  uint32_t win = uint32_t(payload[b0]) << 8;
+  if (b0 + 1 < payload_bytes) win |= payload[b0 + 1];
+  const uint32_t u = (win >> (16 - K - sh)) & ((1u << K) - 1u);
+  const int q = (K == 8) ? int(int8_t(u)) : int(u) - (1 << (K - 1));
+  return __fmul_rn(float(q), s);
+}
+
+template <typename TO, int K, bool PERCH>
+__global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(
+    const uint32_t* __restrict__ payload32, const float* __restrict__ header, TO* __restrict__ xhat, int64_t N,
+    int64_t fast_vecs, int64_t payload_bytes, ChanGeom geom, int64_t m, int64_t seg_len) {
+  constexpr int VEC = Elem<TO>::VEC;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  const float s_tensor = PERCH ? 0.0f : header[0];
+  ChanPos pos{0, 0};
+  if (PERCH && v < fast_vecs) pos = chan_init(geom, v);
+  for (; v < fast_vecs; v += stride) {
+    float s = s_tensor;
+    if (PERCH) {
+      s = header[pos.ch];
+      chan_advance(geom, pos, geom.sgrid);
+    }
+    float f[VEC];
+#pragma unroll
+    for (int h = 0; h < VEC / 4; ++h) dequant4<K>(payload32, v * VEC + 4 * h, s, &f[4 * h]);
+    store_vec(xhat + v * VEC, f);
+  }
+  const uint8_t* payload8 = reinterpret_cast<const uint8_t*>(payload32);
+  for (int64_t i = fast_vecs * VEC + int64_t(blockIdx.x) * kBlock + threadIdx.x; i < N; i += stride) {
+    const float s = PERCH ? header[(i % m) / seg_len] : s_tensor;
+    store_one(xhat + i, dequant1<K>(payload8, i, payload_bytes, s));
+  }
+}
+
+// ============================================================================= host side
+ChanStep make_step(int64_t step_vecs, int64_t seg_vecs, int64_t C) {
+  ChanStep st;
+  st.dr = step_vecs % seg_vecs;
+  st.dch = int32_t((step_vecs / seg_vecs) % C);
+  return st;
+}
+
+template <typename T, int K, bool PERCH, bool STOCH>
+hipError_t launch_quant(const accept_desc& d, const UPlan& p, const T* x, float* header, uint32_t* payload,
+                        const float* partials, const float* rtab, hipStream_t s) {
+  const int64_t N = p.N;
+  const int64_t full_tiles = p.fast ? N / kTileElems : 0;
+  const int64_t groups = (N + 7) / 8;
+  const int64_t slow_first = full_tiles * (kTileElems / 8);
+  const int64_t slow_groups = groups - slow_first;
+  int64_t want = full_tiles > (slow_groups + kBlock - 1) / kBlock ? full_tiles : (slow_groups + kBlock - 1) / kBlock;
+  if (want < 1) want = 1;
+  const int grid = int(want < kQuantGridMax ? want : kQuantGridMax);
+  ChanGeom g{};
+  g.seg_vecs = 1;
+  g.C = 1;
+  if (PERCH && p.fast) {
+    g.seg_vecs = p.seg_len / p.vec;
+    g.C = int32_t(p.C);
+    g.s256 = make_step(kBlock, g.seg_vecs, p.C);
+    g.sgrid = make_step(int64_t(grid) * (kTileElems / p.vec), g.seg_vecs, p.C);
+  }
+  const int64_t payload_bytes = (N * K + 7) / 8;
+  hipLaunchKernelGGL((quantize_pack_kernel<T, K, PERCH, STOCH>), dim3(grid), dim3(kBlock), 0, s, x, payload, header,
+                     partials, p.range_grid, rtab, N, full_tiles, slow_first, payload_bytes, g, p.m, p.seg_len,
+                     d.seed);
+  return hipGetLastError();
+}
+
+template <typename T, int K>
+hipError_t launch_quant_k(const accept_desc& d, const UPlan& p, const T* x, float* header, uint32_t* payload,
+                          const float* partials, const float* rtab, hipStream_t s) {
+  const bool perch = p.mode != U_TENSOR;
+  const bool stoch = d.rounding == ACCEPT_ROUND_STOCHASTIC;
+  if (perch) {
+    return stoch ? launch_quant<T, K, true, true>(d, p, x, header, payload, partials, rtab, s)
+                 : launch_quant<T, K, true, false>(d, p, x, header, payload, partials, rtab, s);
+  }
+  return stoch ? launch_quant<T, K, false, true>(d, p, x, header, payload, partials, rtab, s)
+               : launch_quant<T, K, false, false>(d, p, x, header, payload, partials, rtab, s);
+}
+
+template <typename T>
+hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, float* header, uint32_t* payload,
+                          void* ws, hipStream_t s, StageTimer* tm) {
+  float* partials = reinterpret_cast<float*>(ws);
+  float* rtab = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + p.off_rtab);
+  mark(tm, s);
+  if (p.mode == U_TENSOR) {
+    hipLaunchKernelGGL((range_tensor_kernel<T>), dim3(p.range_grid), dim3(kBlock), 0, s, x, p.N, partials);
+  } else if (p.mode == U_SEGMENTED) {
+    const int64_t blocks = (p.items + (kBlock / kWave) - 1) / (kBlock / kWave);
+    const int grid = int(blocks < 65536 ? blocks : 65536);
+    hipLaunchKernelGGL((range_segments_kernel<T>), dim3(grid), dim3(kBlock), 0, s, x, p.items, p.cps,
+                       p.seg_len / p.vec, p.chunk_vecs, partials);
+  } else {
+    const int zgrid = int((p.C + kBlock - 1) / kBlock < 1024 ? (p.C + kBlock - 1) / kBlock : 1024);
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(zgrid), dim3(kBlock), 0, s, reinterpret_cast<uint32_t*>(partials), p.C);
+    const int64_t blocks = (p.N + kBlock - 1) / kBlock;
+    const int grid = int(blocks < 16384 ? blocks : 16384);
+    hipLaunchKernelGGL((range_generic_kernel<T>), dim3(grid), dim3(kBlock), 0, s, x, p.N, p.m, p.seg_len,
+                       reinterpret_cast<uint32_t*>(partials));
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  mark(tm, s);
+  if (p.mode != U_TENSOR) {
+    // U_GENERIC stores one maximum per channel: finalize reads it as a 1 x C x 1 table.
+    const int64_t rows = p.mode == U_SEGMENTED ? d.n : 1;
+    const int64_t cps = p.mode == U_SEGMENTED ? p.cps : 1;
+    hipLaunchKernelGGL(range_finalize_kernel, dim3(unsigned(p.C)), dim3(kWave), 0, s, partials, rows, p.C, cps,
+                       d.bits, header, rtab);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    mark(tm, s);
+  }
+  switch (d.bits) {
+    case 2: e = launch_quant_k<T, 2>(d, p, x, header, payload, partials, rtab, s); break;
+    case 3: e = launch_quant_k<T, 3>(d, p, x, header, payload, partials, rtab, s); break;
+    case 4: e = launch_quant_k<T, 4>(d, p, x, header, payload, partials, rtab, s); break;
+    case 5: e = launch_quant_k<T, 5>(d, p, x, header, payload, partials, rtab, s); break;
+    case 6: e = launch_quant_k<T, 6>(d, p, x, header, payload, partials, rtab, s); break;
+    case 7: e = launch_quant_k<T, 7>(d, p, x, header, payload, partials, rtab, s); break;
+    case 8: e = launch_quant_k<T, 8>(d, p, x, header, payload, partials, rtab, s); break;
+    default: return hipErrorInvalidValue;
+  }
+  if (e != hipSuccess) return e;
+  mark(tm, s);
+  return hipSuccess;
+}
+
+template <typename TO, int K, bool PERCH>
+hipError_t launch_dequant(const accept_desc& d, const float* header, const uint32_t* payload, TO* xhat,
+                          hipStream_t s) {
+  constexpr int VEC = Elem<TO>::VEC;
+  const int64_t N = d.n * d.m;
+  const int64_t C = d.channels > 1 ? d.channels : 1;
+  const int64_t seg_len = d.m / C;
+  // The vector path covers whole groups of 32 elements (k whole dwords), so that no dword
+  // load reaches past the payload; per channel it also needs vectors that stay in a segment.
+  const bool fast = !PERCH || (seg_len % VEC == 0);
+  const int64_t fast_vecs = fast ? (N / 32) * (32 / VEC) : 0;
+  const int64_t work = fast_vecs > (N - fast_vecs * VEC) ? fast_vecs : (N - fast_vecs * VEC);
+  int64_t blocks = (work + kBlock - 1) / kBlock;
+  if (blocks < 1) blocks = 1;
+  const int grid = int(blocks < kDequantGridMax ? blocks : kDequantGridMax);
+  ChanGeom g{};
+  g.seg_vecs = 1;
+  g.C = 1;
+  if (PERCH && fast) {
+    g.seg_vecs = seg_len / VEC;
+    g.C = int32_t(C);
+    g.sgrid = make_step(int64_t(grid) * kBlock, g.seg_vecs, C);
+    g.s256 = g.sgrid;
+  }
+  const int64_t payload_bytes = (N * K + 7) / 8;
+  hipLaunchKernelGGL((unpack_dequant_kernel<TO, K, PERCH>), dim3(grid), dim3(kBlock), 0, s, payload, header, xhat, N,
+                     fast_vecs, payload_bytes, g, d.m, seg_len);
+  return hipGetLastError();
+}
+
+template <typename TO>
+hipError_t decompress_typed(const accept_desc& d, const float* header, const uint32_t* payload, TO* xhat,
+                            hipStream_t s) {
+  const bool perch = d.channels > 1;
+#define ACCEPT_DQ(KK)                                                              \
+  case KK:                                                                         \
+    return perch ? launch_dequant<TO, KK, true>(d, header, payload, xhat, s)       \
+                 : launch_dequant<TO, KK, false>(d, header, payload, xhat, s);
+  switch (d.bits) {
+    ACCEPT_DQ(2) ACCEPT_DQ(3) ACCEPT_DQ(4) ACCEPT_DQ(5) ACCEPT_DQ(6) ACCEPT_DQ(7) ACCEPT_DQ(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef ACCEPT_DQ
+}
+
+}  // namespace
+
+UPlan make_uplan(const accept_desc& d) {
+  UPlan p{};
+  p.N = d.n * d.m;
+  p.m = d.m;
+  p.C = d.channels > 1 ? d.channels : 1;
+  p.seg_len = d.m / p.C;
+  p.vec = d.in_dtype == ACCEPT_BF16 ? 8 : 4;
+  p.cps = 1;
+  p.chunk_vecs = 1;
+  p.items = 0;
+  p.range_grid = 1;
+  size_t partial_bytes;
+  if (p.C == 1) {
+    p.mode = U_TENSOR;
+    p.fast = true;
+    const int64_t nvec = p.N / p.vec;
+    int64_t blocks = (nvec + int64_t(kBlock) * 4 - 1) / (int64_t(kBlock) * 4);
+    if (blocks < 1) blocks = 1;
+    p.range_grid = int(blocks < kRangeGridMax ? blocks : kRangeGridMax);
+    partial_bytes = size_t(kRangeGridMax) * sizeof(float);
+  } else if (p.seg_len % p.vec == 0 && p.seg_len >= 512) {
+    p.mode = U_SEGMENTED;
+    p.fast = true;
+    const int64_t seg_vecs = p.seg_len / p.vec;
+    const int64_t max_chunk = 4096;  // vectors (64 KiB) one wavefront reduces
+    p.cps = (seg_vecs + max_chunk - 1) / max_chunk;
+    p.chunk_vecs = (seg_vecs + p.cps - 1) / p.cps;
+    p.items = d.n * p.C * p.cps;
+    partial_bytes = size_t(p.items) * sizeof(float);
+  } else {
+    p.mode = U_GENERIC;
+    p.fast = (p.seg_len % p.vec == 0);
+    partial_bytes = size_t(p.C) * sizeof(uint32_t);
+  }
+  p.off_rtab = (partial_bytes + 255) / 256 * 256;
+  p.bytes = p.off_rtab + (size_t(p.C) * sizeof(float) + 255) / 256 * 256;
+  return p;
+}
+
+hipError_t launch_uniform_compress(const accept_desc& d, const UPlan& p, const void* x, void* header, void* payload,
+                                   void* ws, hipStream_t s, StageTimer* tm) {
+  if (d.in_dtype == ACCEPT_BF16)
+    return compress_typed<bf16_t>(d, p, static_cast<const bf16_t*>(x), static_cast<float*>(header),
+                                  static_cast<uint32_t*>(payload), ws, s, tm);
+  return compress_typed<float>(d, p, static_cast<const float*>(x), static_cast<float*>(header),
+                               static_cast<uint32_t*>(payload), ws, s, tm);
+}
+
+hipError_t launch_uniform_decompress(const accept_desc& d, const void* header, const void* payload, void* xhat,
+                                     hipStream_t s, StageTimer* tm) {
+  mark(tm, s);
+  hipError_t e;
+  if (d.out_dtype == ACCEPT_BF16)
+    e = decompress_typed<bf16_t>(d, static_cast<const float*>(header), static_cast<const uint32_t*>(payload),
+                                 static_cast<bf16_t*>(xhat), s);
+  else
+    e = decompress_typed<float>(d, static_cast<const float*>(header), static_cast<const uint32_t*>(payload),
+                                static_cast<float*>(xhat), s);
+  if (e != hipSuccess) return e;
+  mark(tm, s);
+  return hipSuccess;
+}
+
+}  // namespace accept

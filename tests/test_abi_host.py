@@ -1,0 +1,117 @@
+"""C ABI checks that need no GPU: the library loads, exports every symbol the header
+declares, and its host-only entry points agree with the oracle and reject bad arguments."""
+import ctypes
+import os
+import re
+import subprocess
+
+import pytest
+
+from oracle import accept_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "accept.h")
+
+
+@pytest.fixture(scope="module")
+def A():
+    import paper_2311_05827_amd as pkg
+    return pkg
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(accept_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ("accept_packed_size", "accept_workspace_size", "accept_compress", "accept_decompress",
+                 "accept_bits_schedule", "accept_status_string"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol(A):
+    lib = A.binding.lib
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+    out = subprocess.run(["nm", "-D", "--defined-only", A.binding.LIB_PATH], capture_output=True, text=True).stdout
+    exported = set(re.findall(r" T (accept_[a-z_]+)", out))
+    assert set(declared_functions()) <= exported
+    # nothing but the C ABI is exported under the accept_ prefix with C linkage
+    assert exported == set(declared_functions())
+
+
+def test_desc_layout_matches_header(A):
+    assert ctypes.sizeof(A.Desc) == 64
+    assert A.Desc.n.offset == 16 and A.Desc.m.offset == 24 and A.Desc.channels.offset == 32
+    assert A.Desc.rounding.offset == 40 and A.Desc.seed.offset == 48 and A.Desc.t.offset == 56
+
+
+@pytest.mark.parametrize("scheme", [0, 1])
+def test_packed_size_matches_oracle(A, scheme):
+    for bits in range(1 if scheme else 2, 9):
+        for n, m, ch in [(1, 1, 0), (4, 65536, 0), (64, 802816, 256), (16, 390912, 0), (15, 509 * 767, 0),
+                         (3, 35, 5), (9, 7, 0), (128, 8192, 0)]:
+            if scheme == 1:
+                ch = 0
+            d = A.make_desc(scheme, bits, n, m, channels=ch)
+            assert A.accept_packed_size(d) == orc.packed_size(scheme, bits, n, m, ch)
+            ws = A.accept_workspace_size(d)
+            assert ws > 0 and ws % 256 == 0 and ws < (1 << 26)
+
+
+def test_bits_schedule_matches_oracle_and_paper(A):
+    for direction in (0, 1):
+        for c in range(6):
+            assert A.accept_bits_schedule(direction, c) == orc.bits_schedule(direction, c)
+    assert A.accept_bits_schedule(2, 0) == -1 and A.accept_bits_schedule(0, -1) == -1
+
+
+def test_status_strings_and_version(A):
+    assert A.status_string(0) == "ok"
+    assert "invalid" in A.status_string(1)
+    assert A.status_string(99) == "unknown status"
+    assert re.match(r"^\d+\.\d+\.\d+$", A.version())
+
+
+def test_invalid_arguments_are_rejected_before_any_launch(A):
+    lib = A.binding.lib
+    INVALID = 1
+    bad = [
+        A.make_desc(0, 1, 4, 4),             # uniform k=1: s = c/0
+        A.make_desc(0, 9, 4, 4),
+        A.make_desc(1, 0, 4, 4),
+        A.make_desc(1, 9, 4, 4),
+        A.make_desc(0, 4, 0, 4),
+        A.make_desc(0, 4, 4, 0),
+        A.make_desc(0, 4, 1 << 30, 1 << 30),  # n*m beyond 2^40
+        A.make_desc(0, 4, 4, 10, channels=3),  # channels must divide m
+        A.make_desc(1, 3, 4, 12, channels=3),  # MBQ has no per-channel mode
+        A.make_desc(2, 4, 4, 4),
+        A.make_desc(0, 4, 4, 4, in_dtype=7),
+        A.make_desc(0, 4, 4, 4, rounding=5),
+        A.make_desc(1, 3, 4, 4, rounding=1),
+        A.make_desc(1, 3, 4, 4, t=-1),
+    ]
+    h, p = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    for d in bad:
+        assert lib.accept_packed_size(ctypes.byref(d), ctypes.byref(h), ctypes.byref(p)) == INVALID
+        assert lib.accept_workspace_size(ctypes.byref(d), ctypes.byref(h)) == INVALID
+    good = A.make_desc(0, 4, 4, 4)
+    assert lib.accept_packed_size(None, ctypes.byref(h), ctypes.byref(p)) == INVALID
+    assert lib.accept_packed_size(ctypes.byref(good), None, ctypes.byref(p)) == INVALID
+    # null and misaligned device pointers never reach a kernel launch
+    assert lib.accept_compress(ctypes.byref(good), None, None, None, None, None, None) == INVALID
+    assert lib.accept_decompress(ctypes.byref(good), None, None, None, None) == INVALID
+    V = ctypes.c_void_p
+    assert lib.accept_compress(ctypes.byref(good), V(0x1008), None, V(0x2000), V(0x3000), V(0x4000), None) == INVALID
+    assert lib.accept_compress(ctypes.byref(good), V(0x1000), None, V(0x2002), V(0x3000), V(0x4000), None) == INVALID
+    assert lib.accept_compress(ctypes.byref(good), V(0x1000), None, V(0x2000), V(0x3004), V(0x4000), None) == INVALID
+    assert lib.accept_compress(ctypes.byref(good), V(0x1000), None, V(0x2000), V(0x3000), V(0x4010), None) == INVALID
+    mbq = A.make_desc(1, 3, 8, 8)
+    assert lib.accept_compress(ctypes.byref(mbq), V(0x1000), None, V(0x2000), V(0x3000), V(0x4000), None) == INVALID
+    assert lib.accept_mbq_init(ctypes.byref(good), V(0x1000), V(0x2000), V(0x4000), None) == INVALID
+    assert A.accept_stage_name(good, 0, 0) == "range" and A.accept_stage_name(good, 0, 1) == "quantize_pack"
+    assert A.accept_stage_name(good, 0, 2) is None and A.accept_stage_name(mbq, 1, 0) == "mbq_decode"
