@@ -1,0 +1,369 @@
+#!/usr/bin/env python3
+"""Benchmark of the bit-level compression hot path on one MI355X.
+
+A step is one pass of the whole path over one batch at a partition boundary, at the
+ResNet-50-style stage-boundary shape 64x256x56x56 (51.4 M elements, fp32):
+
+    forward features : scheme M (multi-bit, k=4) compress  -> decompress
+    backward gradient: scheme U (uniform,   k=8) compress  -> decompress
+
+Inputs are synthetic (seeded) and already resident in HBM; two buffer sets alternate so
+that nothing a call reads was produced or read by the previous ~1 GB of traffic (the
+256 MB memory-side cache cannot serve a call's first read).  One JSON line is printed:
+value = GB/s of uncompressed fp32 bytes through the step's four calls; the breakdown holds
+each call's own rate and its algorithmic fraction of the 8 TB/s HBM peak; "roofline"
+describes the dominant kernel from HIP-event stage timings taken inside this run;
+"cpu_baseline" is the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--sweep]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+METRIC = "compress / decompress GB/s of fp32 input and % of MI355X HBM peak"
+SHAPE = (64, 256, 56, 56)
+K_FWD, K_BWD = 4, 8
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_cfg4.txt")
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def alg_bytes(kernel, N, n, m, k, b_in=4, b_out=4):
+    """Algorithmic HBM bytes one launch of a kernel must move."""
+    if kernel == "range":
+        return N * b_in
+    if kernel == "quantize_pack":
+        return N * b_in + (N * k + 7) // 8 + 4
+    if kernel == "unpack_dequant":
+        return (N * k + 7) // 8 + 4 + N * b_out
+    if kernel == "mbq_encode":
+        return N * b_in + ((n + 7) // 8) * m * k
+    if kernel == "mbq_decode":
+        return ((n + 7) // 8) * m * k + 4 * (k + 1) + N * b_out
+    return 0
+
+
+def read_traffic():
+    """Measured HBM bytes per launch from committed rocprofv3 --pmc summaries, if present."""
+    out = {}
+    if os.path.exists(TRAFFIC_FILE):
+        for line in open(TRAFFIC_FILE):
+            line = line.split("#", 1)[0].strip()
+            if "=" in line:
+                k, v = line.split("=", 1)
+                try:
+                    out[k.strip()] = float(v)
+                except ValueError:
+                    pass
+    return out
+
+
+class Slot:
+    """One set of device buffers for the four calls of a step."""
+
+    def __init__(self, A, torch, act, grad, alpha, dm, du):
+        self.act = act.clone()
+        self.grad = grad.clone()
+        self.alpha = alpha.clone()
+        self.mh, self.mp, self.mw = A.alloc_outputs(dm, act.device)
+        self.uh, self.up, self.uw = A.alloc_outputs(du, act.device)
+        self.xhat_m = torch.empty(dm.n * dm.m, dtype=torch.float32, device=act.device)
+        self.xhat_u = torch.empty(du.n * du.m, dtype=torch.float32, device=act.device)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--sweep", action="store_true", help="also time every (config, scheme, k) cell; table on stderr")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (the codec has no multi-GPU path); use --gpus 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2311_05827_amd as A
+    import synthetic_inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    n, m = SHAPE[0], SHAPE[1] * SHAPE[2] * SHAPE[3]
+    N = n * m
+
+    t0 = time.time()
+    act_np = si.make("cfg4_act")
+    grad_np = si.make("cfg4_grad")
+    log("inputs generated in %.1fs" % (time.time() - t0))
+    act = torch.from_numpy(act_np.reshape(-1)).to(dev)
+    grad = torch.from_numpy(grad_np.reshape(-1)).to(dev)
+
+    dm = A.make_desc(A.MBQ, K_FWD, n, m, t=1)
+    du = A.make_desc(A.UNIFORM, K_BWD, n, m)
+    alpha0 = A.accept_mbq_init(dm, act)  # residue initialisation on the GPU
+    torch.cuda.synchronize()
+
+    slots = [Slot(A, torch, act, grad, alpha0, dm, du) for _ in range(2)]
+
+    def compress_m(s):
+        A.accept_compress(dm, s.act, alpha_prev=s.alpha, header=s.mh, payload=s.mp, workspace=s.mw)
+
+    def decompress_m(s):
+        A.accept_decompress(dm, s.mh, s.mp, out=s.xhat_m)
+
+    def compress_u(s):
+        A.accept_compress(du, s.grad, header=s.uh, payload=s.up, workspace=s.uw)
+
+    def decompress_u(s):
+        A.accept_decompress(du, s.uh, s.up, out=s.xhat_u)
+
+    def step(j):
+        a, b = slots[j % 2], slots[(j + 1) % 2]
+        compress_m(a)      # forward features of this batch
+        decompress_m(b)    # receiver side: a payload produced a whole step ago
+        compress_u(a)      # backward gradients
+        decompress_u(b)
+
+    # fill both slots so that every decompress has a valid payload
+    for s in slots:
+        compress_m(s)
+        compress_u(s)
+    torch.cuda.synchronize()
+
+    for j in range(args.warmup):
+        step(j)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for j in range(args.steps):
+        step(j)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    step_bytes = 4 * N * 4
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # per-call rates, same rotation (cold inputs), events around K calls of one kind
+    def time_call(fn, other):
+        for j in range(5):
+            fn(slots[j % 2]); other(slots[(j + 1) % 2])
+        torch.cuda.synchronize()
+        tot = 0.0
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(10, args.steps // 4)
+        for j in range(reps):
+            other(slots[(j + 1) % 2])   # evicts: >= 230 MB of unrelated traffic between timed calls
+            other(slots[j % 2])
+            e0.record()
+            fn(slots[j % 2])
+            e1.record()
+            e1.synchronize()
+            tot += e0.elapsed_time(e1)
+        return tot / reps
+
+    calls = {
+        "mbq_compress_k4": (compress_m, decompress_u, alg_bytes("mbq_encode", N, n, m, K_FWD)),
+        "mbq_decompress_k4": (decompress_m, compress_u, alg_bytes("mbq_decode", N, n, m, K_FWD)),
+        "uniform_compress_k8": (compress_u, decompress_m,
+                                alg_bytes("range", N, n, m, K_BWD) + alg_bytes("quantize_pack", N, n, m, K_BWD)),
+        "uniform_decompress_k8": (decompress_u, compress_m, alg_bytes("unpack_dequant", N, n, m, K_BWD)),
+    }
+    breakdown = {}
+    for name, (fn, other, ab) in calls.items():
+        ms = time_call(fn, other)
+        breakdown[name] = {
+            "ms": round(ms, 5),
+            "input_GBps": round(N * 4 / (ms * 1e-3) / 1e9, 1),
+            "alg_bytes": ab,
+            "alg_hbm_frac": round(ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        }
+
+    # per-kernel durations from HIP events recorded by the library around each launch
+    stage_ms = {}
+    reps = max(10, args.steps // 4)
+    for j in range(reps):
+        a, b = slots[j % 2], slots[(j + 1) % 2]
+        for nm_, ms in A.accept_compress_timed(dm, a.act, a.alpha, a.mh, a.mp, a.mw):
+            stage_ms.setdefault(nm_, []).append(ms)
+        for nm_, ms in A.accept_decompress_timed(dm, b.mh, b.mp, b.xhat_m):
+            stage_ms.setdefault(nm_, []).append(ms)
+        for nm_, ms in A.accept_compress_timed(du, a.grad, None, a.uh, a.up, a.uw):
+            stage_ms.setdefault(nm_, []).append(ms)
+        for nm_, ms in A.accept_decompress_timed(du, b.uh, b.up, b.xhat_u):
+            stage_ms.setdefault(nm_, []).append(ms)
+    kernels = {}
+    kbits = {"range": K_BWD, "quantize_pack": K_BWD, "unpack_dequant": K_BWD, "mbq_encode": K_FWD,
+             "mbq_decode": K_FWD}
+    for nm_, v in stage_ms.items():
+        avg = sum(v) / len(v)
+        ab = alg_bytes(nm_, N, n, m, kbits.get(nm_, 0))
+        kernels[nm_] = {"avg_ms": round(avg, 5), "alg_bytes": ab,
+                        "GBps": round(ab / (avg * 1e-3) / 1e9, 1) if ab else None}
+    dominant = max((k_ for k_ in kernels if kernels[k_]["alg_bytes"]), key=lambda k_: kernels[k_]["avg_ms"])
+    traffic = read_traffic().get(dominant)
+    roofline = {
+        "bound": "hbm",
+        "kernel": dominant,
+        "achieved": kernels[dominant]["GBps"],
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": round(kernels[dominant]["GBps"] / HBM_PEAK_GBPS, 4),
+        "traffic": traffic,
+        "alg_bytes_per_launch": kernels[dominant]["alg_bytes"],
+        "avg_launch_ms": kernels[dominant]["avg_ms"],
+        "kernels": kernels,
+    }
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(np, act_np, grad_np, n, m)
+
+    if args.sweep:
+        sweep(A, torch, si, np)
+
+    out = {
+        "metric": METRIC,
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "cfg4 stage-boundary tensor 64x256x56x56 fp32 (51.4M elems): per step MBQ k=4 compress+"
+                        "decompress of post-ReLU features and uniform k=8 compress+decompress of gradients",
+            "elements": N,
+            "uncompressed_bytes_per_step": step_bytes,
+            "cold_inputs": "two buffer sets alternate; decompress reads a payload written one step earlier",
+        },
+        "hbm_frac_of_value": round(value / HBM_PEAK_GBPS, 4),
+        "breakdown": breakdown,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(np, act_np, grad_np, n, m):
+    """The oracle as it stands, on the first 8 batch rows of the same two tensors."""
+    from oracle import accept_oracle as orc
+    rows = 8
+    a = np.ascontiguousarray(act_np.reshape(n, m)[:rows])
+    g = np.ascontiguousarray(grad_np.reshape(n, m)[:rows])
+    t0 = time.perf_counter()
+    alpha0, _ = orc.mbq_residue_init(a, K_FWD)
+    t_init = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    mh, mp = orc.mbq_compress(a, K_FWD, rows, m, alpha0, 1)
+    orc.mbq_decompress(mh, mp, K_FWD, rows, m)
+    uh, up = orc.uniform_compress(g, K_BWD, rows, m)
+    orc.uniform_decompress(uh, up, K_BWD, rows, m)
+    dt = time.perf_counter() - t0
+    nbytes = 4 * rows * m * 4
+    log("cpu oracle: %.2fs for %d elements x 4 calls (init %.2fs not counted)" % (dt, rows * m, t_init))
+    return {
+        "value": round(nbytes / dt / 1e9, 4),
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "first 8 of 64 batch rows (6.4M elements) of the same two tensors, same four calls, "
+                  "NumPy oracle, single thread",
+        "seconds": round(dt, 3),
+    }
+
+
+def sweep(A, torch, si, np):
+    """Cold-input timings of every (config, scheme, k, dtype, range mode) cell; stderr table."""
+    dev = torch.device("cuda:0")
+    scratch = torch.empty(160 * 1024 * 1024, dtype=torch.float32, device=dev)  # 640 MB cache flusher
+
+    def flush():
+        scratch.add_(1.0)
+
+    def timeit(fn, reps=20):
+        fn(); torch.cuda.synchronize()
+        tot = []
+        for _ in range(reps):
+            flush()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); fn(); e1.record(); e1.synchronize()
+            tot.append(e0.elapsed_time(e1))
+        tot.sort()
+        return tot[len(tot) // 2]
+
+    cells = []
+    plans = [
+        ("cfg1_act", [("U", 8, 0, False), ("M", 2, 0, False), ("M", 3, 0, False), ("M", 4, 0, False)]),
+        ("cfg2_grad", [("U", 4, 0, False), ("U", 2, 0, False)]),
+        ("cfg3_act", [("U", k, 0, False) for k in range(2, 9)] + [("M", k, 0, False) for k in (2, 3, 4)]),
+        ("cfg4_act", [("U", k, c, b) for k in (4, 6, 8) for c in (0, 256) for b in (False, True)]
+         + [("M", k, 0, False) for k in (2, 3, 4)]),
+        ("cfg4_grad", [("U", k, c, False) for k in (4, 6, 8) for c in (0, 256)]),
+        ("cfg5_hidden", [("U", k, 0, False) for k in (3, 5, 6, 7)] + [("M", 3, 0, False)]),
+        ("cfg5_grad", [("U", k, 0, False) for k in (3, 5, 6, 7)]),
+    ]
+    log("%-12s %-2s %1s %4s %5s | %9s %9s %7s | %9s %9s %7s" % (
+        "config", "S", "k", "C", "dtype", "comp_us", "in_GB/s", "alg%", "decomp_us", "out_GB/s", "alg%"))
+    for name, cases in plans:
+        x_np = si.make(name)
+        n, m = si.as_nm(x_np)
+        N = n * m
+        x32 = torch.from_numpy(x_np.reshape(-1)).to(dev)
+        x16 = x32.to(torch.bfloat16)
+        for scheme, k, C, bf in cases:
+            x = x16 if bf else x32
+            b = 2 if bf else 4
+            if scheme == "U":
+                d = A.make_desc(A.UNIFORM, k, n, m, channels=C, in_dtype=A.BF16 if bf else A.F32,
+                                out_dtype=A.BF16 if bf else A.F32)
+                alpha = None
+                cb = alg_bytes("range", N, n, m, k, b) + alg_bytes("quantize_pack", N, n, m, k, b)
+                db = alg_bytes("unpack_dequant", N, n, m, k, b, b)
+            else:
+                d = A.make_desc(A.MBQ, k, n, m, t=1)
+                alpha = A.accept_mbq_init(d, x)
+                cb = alg_bytes("mbq_encode", N, n, m, k, b)
+                db = alg_bytes("mbq_decode", N, n, m, k, b, b)
+            h, p, w = A.alloc_outputs(d, dev)
+            out = torch.empty(N, dtype=torch.bfloat16 if bf else torch.float32, device=dev)
+            tc = timeit(lambda: A.accept_compress(d, x, alpha_prev=alpha, header=h, payload=p, workspace=w))
+            td = timeit(lambda: A.accept_decompress(d, h, p, out=out))
+            cell = dict(config=name, scheme=scheme, k=k, channels=C, dtype="bf16" if bf else "f32",
+                        compress_us=round(tc * 1e3, 2), decompress_us=round(td * 1e3, 2),
+                        compress_in_GBps=round(N * b / tc / 1e6, 1), decompress_out_GBps=round(N * b / td / 1e6, 1),
+                        compress_alg_frac=round(cb / tc / 1e6 / HBM_PEAK_GBPS, 4),
+                        decompress_alg_frac=round(db / td / 1e6 / HBM_PEAK_GBPS, 4))
+            cells.append(cell)
+            log("%-12s %-2s %1d %4d %5s | %9.1f %9.1f %6.1f%% | %9.1f %9.1f %6.1f%%" % (
+                name, scheme, k, C, cell["dtype"], tc * 1e3, cell["compress_in_GBps"],
+                100 * cell["compress_alg_frac"], td * 1e3, cell["decompress_out_GBps"],
+                100 * cell["decompress_alg_frac"]))
+        del x32, x16
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "sweep.json"), "w") as f:
+        json.dump(cells, f, indent=1)
+
+
+if __name__ == "__main__":
+    main()

@@ -38,20 +38,23 @@ def hipcc_path():
     raise RuntimeError("hipcc not found (looked at $HIPCC, /opt/rocm/bin/hipcc, PATH)")
 
 
-def _compile(hipcc, src, obj):
-    cmd = [hipcc] + HIPCC_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(hipcc, src, obj, extra):
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     return src, r.returncode, (r.stdout + r.stderr), " ".join(cmd)
 
 
-def build(verbose=True):
-    """Compile every HIP source and link libaccept.so.  Always recompiles."""
+def build(verbose=True, extra_flags=(), lib_path=LIB_PATH, build_dir=None):
+    """Compile every HIP source and link libaccept.so.  Always recompiles.
+
+    extra_flags (e.g. ``-DACCEPT_RANGE_GRID=512``) and lib_path exist for tuning sweeps that
+    build variants side by side; the product is the default call."""
     hipcc = hipcc_path()
-    bdir = os.path.join(HERE, "_build")
+    bdir = build_dir or os.path.join(HERE, "_build")
     os.makedirs(bdir, exist_ok=True)
     objs = [os.path.join(bdir, s.replace(".hip", ".o")) for s in SOURCES]
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        results = list(ex.map(lambda so: _compile(hipcc, so[0], so[1]), zip(SOURCES, objs)))
+        results = list(ex.map(lambda so: _compile(hipcc, so[0], so[1], extra_flags), zip(SOURCES, objs)))
     for src, rc, out, cmd in results:
         noise = "packed-fp32-ops' is not a recognized feature"
         shown = "\n".join(l for l in out.splitlines() if noise not in l)
@@ -59,15 +62,15 @@ def build(verbose=True):
             raise RuntimeError("hipcc failed on %s\n%s\n%s" % (src, cmd, out))
         if verbose and shown.strip():
             print(shown, file=sys.stderr)
-    tmp = LIB_PATH + ".tmp"
+    tmp = lib_path + ".tmp"
     link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
     r = subprocess.run(link, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed\n%s\n%s" % (" ".join(link), r.stdout + r.stderr))
-    os.replace(tmp, LIB_PATH)
+    os.replace(tmp, lib_path)
     if verbose:
-        print("built", LIB_PATH, file=sys.stderr)
-    return LIB_PATH
+        print("built", lib_path, file=sys.stderr)
+    return lib_path
 
 
 if __name__ == "__main__":

@@ -15,9 +15,23 @@ namespace accept {
 
 namespace {
 
-constexpr int kEncodeGridMax = 2048;
-constexpr int kDecodeGridMax = 8192;
+// Launch-shape constants; the -D overrides exist for tuning sweeps only.
+#ifndef ACCEPT_ENCODE_GRID
+#define ACCEPT_ENCODE_GRID 512
+#endif
+#ifndef ACCEPT_ENCODE_WAVES
+#define ACCEPT_ENCODE_WAVES 2  // wavefronts per SIMD the encode kernel is compiled for
+#endif
+#ifndef ACCEPT_ENCODE_SCHED_ROWS
+#define ACCEPT_ENCODE_SCHED_ROWS 2  // rows whose table lookups the scheduler may interleave
+#endif
+#ifndef ACCEPT_DECODE_GRID
+#define ACCEPT_DECODE_GRID 8192
+#endif
+constexpr int kEncodeGridMax = ACCEPT_ENCODE_GRID;  // also the number of partial-sum records
+constexpr int kDecodeGridMax = ACCEPT_DECODE_GRID;
 constexpr int kInitGrid = 1024;
+static_assert(kEncodeGridMax <= 2048, "the workspace holds at most 2048 records");
 
 template <int NDW>
 struct alignas((NDW % 4 == 0) ? 16 : (NDW % 2 == 0) ? 8 : 4) Dwords {
@@ -70,136 +84,153 @@ __device__ __forceinline__ void build_levels(const float* __restrict__ alpha, fl
 }
 
 // ================================================================ encode + sums (M1..M4)
-template <typename T, int K, int VEC>
-__global__ __launch_bounds__(kBlock) void mbq_encode_kernel(const T* __restrict__ x,
-                                                             const float* __restrict__ alpha_prev,
-                                                             uint8_t* __restrict__ payload,
-                                                             double* __restrict__ partials, int64_t n, int64_t m,
-                                                             int64_t ipg, int64_t items, ItemStep step) {
-  constexpr int P = 1 << K;
-  constexpr int NW = (K + 3) / 4;            // 32-bit words of a spread pattern
-  constexpr int NPAIR = K * (K - 1) / 2;
-  constexpr int NSTAT = nstat_of(K);
-  constexpr int NDW = (VEC * K + 3) / 4;     // output dwords per item (VEC >= 4)
-  __shared__ float lv_raw[P];
-  __shared__ float lv_sorted[P];
-  __shared__ uint32_t pat_sorted[P];
-  __shared__ float tau[P];
-  __shared__ uint32_t spread[NW][P];
-  __shared__ double red[kBlock / kWave][NSTAT];
+// M2 without a per-element binary search.  The top 13 bits of a float32 (sign, exponent, four
+// mantissa bits) name a bucket, i.e. an interval of reals.  For every bucket a table holds
+// lo = number of thresholds below the whole bucket; the element's position among the sorted
+// levels is then lo + #{c < maxcnt : x > tau[lo + c]}, where maxcnt is the largest number of
+// thresholds that fall inside any one bucket (1 for well separated levels) and tau is padded
+// with +inf.  The float compares decide; the table only says where to start, so the result is
+// exactly #{i : x > tau_i}.
+#ifndef ACCEPT_LUT_BITS
+#define ACCEPT_LUT_BITS 13
+#endif
+constexpr int kLutBits = ACCEPT_LUT_BITS;
+constexpr int kLutSize = 1 << kLutBits;
 
+template <int K>
+struct EncodeTables {
+  static constexpr int P = 1 << K;
+  static constexpr int NW = (K + 3) / 4;  // spread words per level
+  float lv_raw[P];
+  float lv_sorted[P];
+  uint32_t pat_sorted[P];
+  float tau[2 * P];                        // P-1 thresholds, then +inf padding
+  uint32_t spread[P * NW];                 // per sorted level: bit p of the sign pattern at bit 8*(p%4) of word p/4
+  uint8_t lut[kLutSize];
+  int maxcnt;
+};
+
+// Value-order successor of a bucket (buckets of negative values run backwards in bit order).
+__device__ __forceinline__ int bucket_next(int b) {
+  constexpr int HALF = kLutSize / 2;
+  if (b >= HALF) return (b == HALF) ? 0 : b - 1;  // negative side: towards -0, then +0
+  return b + 1;                                    // positive side (HALF-1 has no successor)
+}
+
+template <int K>
+__device__ __forceinline__ void build_encode_tables(const float* __restrict__ alpha_prev, EncodeTables<K>& tb) {
+  using TB = EncodeTables<K>;
+  constexpr int P = TB::P;
   const int tid = threadIdx.x;
-  build_levels<K>(alpha_prev, lv_raw, lv_sorted, pat_sorted);
+  if (tid == 0) tb.maxcnt = 1;
+  build_levels<K>(alpha_prev, tb.lv_raw, tb.lv_sorted, tb.pat_sorted);
+  for (int i = tid; i < 2 * P; i += kBlock)
+    tb.tau[i] = (i < P - 1) ? __fmul_rn(0.5f, __fadd_rn(tb.lv_sorted[i], tb.lv_sorted[i + 1])) : __builtin_inff();
   if (tid < P) {
-    // thresholds: float32 midpoints of neighbouring levels; entry P-1 is never read
-    tau[tid] = (tid < P - 1) ? __fmul_rn(0.5f, __fadd_rn(lv_sorted[tid], lv_sorted[tid + 1])) : 0.0f;
-    const uint32_t pat = pat_sorted[tid];
+    const uint32_t pat = tb.pat_sorted[tid];
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
+    for (int w = 0; w < TB::NW; ++w) {
       uint32_t sp = 0;
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
-        if (4 * w + b < K) sp |= ((pat >> (4 * w + b)) & 1u) << (8 * b);
-      spread[w][tid] = sp;
+      for (int bb = 0; bb < 4; ++bb)
+        if (4 * w + bb < K) sp |= ((pat >> (4 * w + bb)) & 1u) << (8 * bb);
+      tb.spread[tid * TB::NW + w] = sp;
     }
   }
   __syncthreads();
+  // lo(b) = #{tau_i < smallest value of bucket b}: tau[0..P-1) is sorted and tau[P-1] = +inf, so a
+  // branch-free binary search over P entries does it
+#pragma unroll 8
+  for (int b = tid; b < kLutSize; b += kBlock) {
+    const uint32_t lo_bits = uint32_t(b) << (32 - kLutBits);
+    const uint32_t hi_bits = lo_bits | ((1u << (32 - kLutBits)) - 1u);
+    const bool neg = (b >> (kLutBits - 1)) != 0;
+    const float vmin = u32_as_f32(neg ? hi_bits : lo_bits);
+    int lo = 0;
+#pragma unroll
+    for (int s = P >> 1; s >= 1; s >>= 1) lo += (tb.tau[lo + s - 1] < vmin) ? s : 0;
+    tb.lut[b] = uint8_t(lo);
+  }
+  __syncthreads();
+  // thresholds inside bucket b = lo(successor) - lo(b); the top positive bucket (NaN patterns)
+  // holds none.  Buckets of NaN patterns have lo = 0 and are skipped as successors.
+  int mymax = 0;
+  for (int b = tid; b < kLutSize; b += kBlock) {
+    if (b == kLutSize / 2 - 1) continue;
+    const int cnt = int(tb.lut[bucket_next(b)]) - int(tb.lut[b]);
+    mymax = cnt > mymax ? cnt : mymax;
+  }
+  if (mymax > 1) atomicMax(&tb.maxcnt, mymax);
+  __syncthreads();
+}
 
-  double A[K];       // sum of x over elements whose plane-p sign is +1
-  double Sx = 0.0;   // sum of x
-  uint32_t cnt[K];   // number of +1 signs per plane
-  uint32_t dis[NPAIR > 0 ? NPAIR : 1];  // number of elements whose planes p<q disagree
-#pragma unroll
-  for (int p = 0; p < K; ++p) { A[p] = 0.0; cnt[p] = 0; }
-#pragma unroll
-  for (int i = 0; i < (NPAIR > 0 ? NPAIR : 1); ++i) dis[i] = 0;
+// Statistics carried by one thread.
+template <int K>
+struct EncodeStats {
+  static constexpr int NPAIR = K * (K - 1) / 2;
+  double H[K];      // sum of x over the +1 entries of plane p
+  double Sx;        // 1^T x
+  uint32_t cnt[K];  // +1 signs per plane
+  uint32_t dis[NPAIR > 0 ? NPAIR : 1];  // elements whose planes p<q disagree
+};
 
-  int64_t it = int64_t(blockIdx.x) * kBlock + tid;
-  ItemPos pos;
-  pos.g = it / ipg;
-  pos.jv = it - pos.g * ipg;
-  for (; it < items; it += int64_t(gridDim.x) * kBlock, item_advance(pos, step, ipg)) {
-    const int64_t row0 = pos.g * 8;
-    const T* xc = x + pos.jv * VEC;
-    float f[8][VEC];
+// M2 for one element: sorted-level position via the bucket table, then the level's spread
+// sign pattern.  Adds x to the running float32 sums: S_x always, A_p where plane p is +1
+// (byte p of the spread word is 0 or 1; converting it to float and using a fused
+// multiply-add gives x*1 or x*0 exactly, so each step rounds like a plain add).
+template <int K, bool ONE>
+__device__ __forceinline__ void encode_elem(const EncodeTables<K>& tb, float x, int maxcnt,
+                                            uint32_t (&sp)[(K + 3) / 4], float (&a32)[K], float& sx32) {
+  using TB = EncodeTables<K>;
+  const int lo = tb.lut[f32_as_u32(x) >> (32 - kLutBits)];
+  int idx = lo + ((x > tb.tau[lo]) ? 1 : 0);
+  if (!ONE) {
+#pragma nounroll
+    for (int c = 1; c < maxcnt; ++c) idx += (x > tb.tau[lo + c]) ? 1 : 0;
+  }
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      if (row0 + r < n) {
-        if constexpr (VEC > 1) {
-          load_vec(xc + (row0 + r) * m, f[r]);
-        } else {
-          f[r][0] = load_one(xc + (row0 + r) * m);
-        }
-      } else {
+  for (int w = 0; w < TB::NW; ++w) sp[w] = tb.spread[idx * TB::NW + w];
+  sx32 = __fadd_rn(sx32, x);
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) f[r][c] = 0.0f;
-      }
-    }
-    uint32_t acc[VEC][NW];
+  for (int p = 0; p < K; ++p) a32[p] = __fmaf_rn(x, float((sp[p / 4] >> (8 * (p % 4))) & 0xFFu), a32[p]);
+}
+
+// End of an item: bit counts from the finished plane bytes, payload store, float32 partial
+// sums (at most 8*VEC terms) folded into the thread's float64 sums.
+template <int K, int VEC>
+__device__ __forceinline__ void finish_item(const uint32_t (&acc)[VEC][(K + 3) / 4], const float (&h32)[K], float sx32,
+                                            uint8_t* __restrict__ dst, EncodeStats<K>& st) {
+  constexpr int NDW = (VEC * K + 3) / 4;
+  constexpr int CW = (VEC + 3) / 4;
+  uint32_t pw[K][CW];  // plane bytes of all VEC columns, plane-major
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) {
+  for (int p = 0; p < K; ++p) {
 #pragma unroll
-      for (int w = 0; w < NW; ++w) acc[c][w] = 0;
-      float a32[K];
-      float sx32 = 0.0f;
+    for (int w = 0; w < CW; ++w) pw[p][w] = 0;
 #pragma unroll
-      for (int p = 0; p < K; ++p) a32[p] = 0.0f;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        uint32_t sp[NW];
-#pragma unroll
-        for (int w = 0; w < NW; ++w) sp[w] = 0;
-        if (row0 + r < n) {
-          const float v = f[r][c];
-          // M2: position among the sorted levels = number of thresholds strictly below v
-          int idx = 0;
-#pragma unroll
-          for (int s = P >> 1; s >= 1; s >>= 1) idx += (v > tau[idx + s - 1]) ? s : 0;
-#pragma unroll
-          for (int w = 0; w < NW; ++w) sp[w] = spread[w][idx];
-          sx32 = __fadd_rn(sx32, v);
-#pragma unroll
-          for (int p = 0; p < K; ++p) {
-            const int msk = __builtin_amdgcn_sbfe(int(sp[p / 4]), 8 * (p % 4), 1);  // 0 or -1
-            a32[p] = __fadd_rn(a32[p], u32_as_f32(f32_as_u32(v) & uint32_t(msk)));
-          }
-        }
-        // M3: row r of the group lands at bit 7-r of each plane byte
-#pragma unroll
-        for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[w];
-      }
-      Sx += double(sx32);
-#pragma unroll
-      for (int p = 0; p < K; ++p) A[p] += double(a32[p]);
-    }
-    // plane bytes of all VEC columns, plane-major, for the counts
-    constexpr int CW = (VEC + 3) / 4;
-    uint32_t pw[K][CW];
+    for (int c = 0; c < VEC; ++c) pw[p][c / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (c % 4));
+  }
+  {
+    int pi = 0;
 #pragma unroll
     for (int p = 0; p < K; ++p) {
 #pragma unroll
-      for (int w = 0; w < CW; ++w) pw[p][w] = 0;
+      for (int w = 0; w < CW; ++w) st.cnt[p] += __popc(pw[p][w]);
 #pragma unroll
-      for (int c = 0; c < VEC; ++c) pw[p][c / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (c % 4));
-    }
-    {
-      int pi = 0;
+      for (int q = p + 1; q < K; ++q) {
 #pragma unroll
-      for (int p = 0; p < K; ++p) {
-#pragma unroll
-        for (int w = 0; w < CW; ++w) cnt[p] += __popc(pw[p][w]);
-#pragma unroll
-        for (int q = p + 1; q < K; ++q) {
-#pragma unroll
-          for (int w = 0; w < CW; ++w) dis[pi] += __popc(pw[p][w] ^ pw[q][w]);
-          ++pi;
-        }
+        for (int w = 0; w < CW; ++w) st.dis[pi] += __popc(pw[p][w] ^ pw[q][w]);
+        ++pi;
       }
     }
-    // payload: byte ((g*m + j)*K + p); the item's VEC*K bytes are contiguous
-    uint8_t* dst = payload + ((pos.g * m + pos.jv * VEC) * K);
-    if constexpr (VEC > 1) {
-      Dwords<NDW> out;
+  }
+  // payload: byte ((g*m + j)*K + p); the item's VEC*K bytes are contiguous
+  if constexpr (VEC > 1) {
+    Dwords<NDW> out;
+    if constexpr (K == 4) {
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) out.v[c] = acc[c][0];
+    } else {
 #pragma unroll
       for (int w = 0; w < NDW; ++w) out.v[w] = 0;
 #pragma unroll
@@ -209,25 +240,158 @@ __global__ __launch_bounds__(kBlock) void mbq_encode_kernel(const T* __restrict_
           const int b = c * K + p;
           out.v[b / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (b % 4));
         }
-      *reinterpret_cast<Dwords<NDW>*>(dst) = out;
-    } else {
+    }
+    *reinterpret_cast<Dwords<NDW>*>(dst) = out;
+  } else {
 #pragma unroll
-      for (int p = 0; p < K; ++p) dst[p] = uint8_t(acc[0][p / 4] >> (8 * (p % 4)));
+    for (int p = 0; p < K; ++p) dst[p] = uint8_t(acc[0][p / 4] >> (8 * (p % 4)));
+  }
+  st.Sx += double(sx32);
+#pragma unroll
+  for (int p = 0; p < K; ++p) st.H[p] += double(h32[p]);
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_row(const T* p, float (&f)[VEC]) {
+  if constexpr (VEC > 1) {
+    load_vec(p, f);
+  } else {
+    f[0] = load_one(p);
+  }
+}
+
+// Plain (not pipelined) item: any number of valid rows, any maxcnt.
+template <typename T, int K, int VEC>
+__device__ __forceinline__ void encode_item_plain(const EncodeTables<K>& tb, const T* __restrict__ x,
+                                                  uint8_t* __restrict__ payload, int64_t n, int64_t m, int64_t g,
+                                                  int64_t jv, int maxcnt, EncodeStats<K>& st) {
+  constexpr int NW = (K + 3) / 4;
+  const int64_t row0 = g * 8;
+  const int nrows = (n - row0) < 8 ? int(n - row0) : 8;
+  const T* xc = x + row0 * m + jv * VEC;
+  uint32_t acc[VEC][NW];
+  float h32[K];
+  float sx32 = 0.0f;
+#pragma unroll
+  for (int p = 0; p < K; ++p) h32[p] = 0.0f;
+#pragma unroll
+  for (int c = 0; c < VEC; ++c)
+#pragma unroll
+    for (int w = 0; w < NW; ++w) acc[c][w] = 0;
+  for (int r = 0; r < 8; ++r) {
+    float f[VEC];
+    if (r < nrows) load_row<T, VEC>(xc + r * m, f);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      uint32_t sp[NW];
+#pragma unroll
+      for (int w = 0; w < NW; ++w) sp[w] = 0;
+      if (r < nrows) encode_elem<K, false>(tb, f[c], maxcnt, sp, h32, sx32);
+      // M3: row r of the group lands at bit 7-r of each plane byte; missing rows give 0 bits
+#pragma unroll
+      for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[w];
     }
   }
+  finish_item<K, VEC>(acc, h32, sx32, payload + ((g * m + jv * VEC) * K), st);
+}
+
+// Fused M1..M4.  Items whose eight rows all exist run through a software-pipelined loop:
+// row r of the next item is requested as soon as row r of the current item has been
+// consumed, so a wavefront always has loads in flight while it works; the first item's rows
+// are requested before the tables are built.  The last, partial row group (n % 8 != 0) and
+// the rare case of several thresholds per bucket take the plain path.
+template <typename T, int K, int VEC>
+__global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel(const T* __restrict__ x,
+                                                             const float* __restrict__ alpha_prev,
+                                                             uint8_t* __restrict__ payload,
+                                                             double* __restrict__ partials, int64_t n, int64_t m,
+                                                             int64_t ipg, int64_t items, ItemStep step) {
+  constexpr int NW = (K + 3) / 4;
+  constexpr int NPAIR = K * (K - 1) / 2;
+  constexpr int NSTAT = nstat_of(K);
+  __shared__ EncodeTables<K> tb;
+  __shared__ double red[kBlock / kWave][NSTAT];
+
+  const int tid = threadIdx.x;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  const int64_t items_full = (n / 8) * ipg;  // items of complete row groups come first
+  int64_t it = int64_t(blockIdx.x) * kBlock + tid;
+  ItemPos pos;
+  pos.g = it / ipg;
+  pos.jv = it - pos.g * ipg;
+
+  float f[8][VEC];
+  bool have = it < items_full;
+  if (have) {
+    const T* xc = x + pos.g * 8 * m + pos.jv * VEC;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) load_row<T, VEC>(xc + r * m, f[r]);
+  }
+
+  build_encode_tables<K>(alpha_prev, tb);
+  const int maxcnt = tb.maxcnt;
+
+  EncodeStats<K> st;
+  st.Sx = 0.0;
+#pragma unroll
+  for (int p = 0; p < K; ++p) { st.H[p] = 0.0; st.cnt[p] = 0; }
+#pragma unroll
+  for (int i = 0; i < (NPAIR > 0 ? NPAIR : 1); ++i) st.dis[i] = 0;
+
+  if (maxcnt == 1) {
+    while (have) {
+      const int64_t nit = it + stride;
+      ItemPos npos = pos;
+      item_advance(npos, step, ipg);
+      const bool nhave = nit < items_full;
+      const T* nxc = x + npos.g * 8 * m + npos.jv * VEC;
+      uint32_t acc[VEC][NW];
+      float h32[K];
+      float sx32 = 0.0f;
+#pragma unroll
+      for (int p = 0; p < K; ++p) h32[p] = 0.0f;
+#pragma unroll
+      for (int c = 0; c < VEC; ++c)
+#pragma unroll
+        for (int w = 0; w < NW; ++w) acc[c][w] = 0;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+          uint32_t sp[NW];
+          encode_elem<K, true>(tb, f[r][c], 1, sp, h32, sx32);
+#pragma unroll
+          for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[w];
+        }
+        if (nhave) load_row<T, VEC>(nxc + r * m, f[r]);
+        // keep the instruction scheduler from interleaving rows: it would otherwise hoist the
+        // table reads of all 8*VEC elements and run out of registers
+        if ((r + 1) % ACCEPT_ENCODE_SCHED_ROWS == 0) __builtin_amdgcn_sched_barrier(0);
+      }
+      finish_item<K, VEC>(acc, h32, sx32, payload + ((pos.g * m + pos.jv * VEC) * K), st);
+      it = nit;
+      pos = npos;
+      have = nhave;
+    }
+  } else {
+    for (; it < items_full; it += stride, item_advance(pos, step, ipg))
+      encode_item_plain<T, K, VEC>(tb, x, payload, n, m, pos.g, pos.jv, maxcnt, st);
+  }
+  for (int64_t jv = int64_t(blockIdx.x) * kBlock + tid; jv < items - items_full; jv += stride)
+    encode_item_plain<T, K, VEC>(tb, x, payload, n, m, n / 8, jv, maxcnt, st);
 
   // M4: workgroup totals in a fixed order -> one record per workgroup, stat-major
-  double st[NSTAT];
+  double sv[NSTAT];
 #pragma unroll
-  for (int p = 0; p < K; ++p) st[p] = A[p];
-  st[K] = Sx;
+  for (int p = 0; p < K; ++p) sv[p] = st.H[p];
+  sv[K] = st.Sx;
 #pragma unroll
-  for (int p = 0; p < K; ++p) st[K + 1 + p] = double(cnt[p]);
+  for (int p = 0; p < K; ++p) sv[K + 1 + p] = double(st.cnt[p]);
 #pragma unroll
-  for (int i = 0; i < NPAIR; ++i) st[2 * K + 1 + i] = double(dis[i]);
+  for (int i = 0; i < NPAIR; ++i) sv[2 * K + 1 + i] = double(st.dis[i]);
 #pragma unroll
   for (int s = 0; s < NSTAT; ++s) {
-    const double w = wave_sum(st[s]);
+    const double w = wave_sum(sv[s]);
     if ((tid & (kWave - 1)) == 0) red[tid / kWave][s] = w;
   }
   __syncthreads();
@@ -240,79 +404,100 @@ __global__ __launch_bounds__(kBlock) void mbq_encode_kernel(const T* __restrict_
 }
 
 // ========================================================================= finalize (M5)
-// One workgroup: fixed-order float64 totals, alpha_cur = (B^T B)^-1 B^T x by Gaussian
-// elimination with partial pivoting, moving average with beta = min(0.9, (1+t)/(10+t)),
-// m_q = mean(B alpha_t - x); header = [alpha_t, m_q].
-__global__ __launch_bounds__(kBlock) void mbq_finalize_kernel(const double* __restrict__ partials, int nrec, int k,
+// One workgroup: fixed-order float64 totals (one wavefront per statistic), then one thread
+// solves alpha_cur = (B^T B)^-1 B^T x by Gaussian elimination with row pivoting, applies the
+// moving average with beta = min(0.9, (1+t)/(10+t)) and m_q = mean(B alpha_t - x);
+// header = [alpha_t, m_q].  K is a template parameter so that the k x k system lives in
+// registers.
+template <int K>
+__global__ __launch_bounds__(kBlock) void mbq_finalize_kernel(const double* __restrict__ partials, int nrec,
                                                                const float* __restrict__ alpha_prev, double n_elems,
                                                                double t, float* __restrict__ header) {
-  __shared__ double red[kBlock];
-  __shared__ double tot[nstat_of(8)];
+  constexpr int NSTAT = nstat_of(K);
+  __shared__ double tot[NSTAT];
   const int tid = threadIdx.x;
-  const int nstat = nstat_of(k);
-  for (int s = 0; s < nstat; ++s) {
-    double a = 0.0;
-    for (int b = tid; b < nrec; b += kBlock) a += partials[int64_t(s) * nrec + b];
-    red[tid] = a;
-    __syncthreads();
-    for (int off = kBlock / 2; off > 0; off >>= 1) {
-      if (tid < off) red[tid] += red[tid + off];
-      __syncthreads();
-    }
-    if (tid == 0) tot[s] = red[0];
-    __syncthreads();
+  // every thread sums records tid, tid+256, ... of every statistic (all loads independent, so
+  // they overlap), then a fixed butterfly per wavefront and a fixed order across wavefronts
+  __shared__ double red[kBlock / kWave][NSTAT];
+  double a[NSTAT];
+#pragma unroll
+  for (int s = 0; s < NSTAT; ++s) a[s] = 0.0;
+  for (int b = tid; b < nrec; b += kBlock) {
+#pragma unroll
+    for (int s = 0; s < NSTAT; ++s) a[s] += partials[int64_t(s) * nrec + b];
   }
+#pragma unroll
+  for (int s = 0; s < NSTAT; ++s) {
+    const double w = wave_sum(a[s]);
+    if ((tid & (kWave - 1)) == 0) red[tid / kWave][s] = w;
+  }
+  __syncthreads();
+  if (tid < NSTAT) {
+    double v = red[0][tid];
+#pragma unroll
+    for (int w = 1; w < kBlock / kWave; ++w) v += red[w][tid];
+    tot[tid] = v;
+  }
+  __syncthreads();
   if (tid != 0) return;
-  double G[8][8], h[8], Sb[8], a_prev[8], cur[8];
-  const double Sx = tot[k];
-  int pi = 0;
-  for (int p = 0; p < k; ++p) {
-    a_prev[p] = double(alpha_prev[p]);
-    h[p] = 2.0 * tot[p] - Sx;                 // B^T x = 2 * (sum over +1 entries) - sum(x)
-    Sb[p] = 2.0 * tot[k + 1 + p] - n_elems;   // 1^T B
-    G[p][p] = n_elems;
-    for (int q = p + 1; q < k; ++q) {
-      G[p][q] = G[q][p] = n_elems - 2.0 * tot[2 * k + 1 + pi];
-      ++pi;
+  double G[K][K], b[K], Sb[K], a_prev[K], cur[K];
+  const double Sx = tot[K];
+  {
+    int pi = 0;
+#pragma unroll
+    for (int p = 0; p < K; ++p) {
+      a_prev[p] = double(alpha_prev[p]);
+      b[p] = 2.0 * tot[p] - Sx;                 // B^T x = 2 * (sum over +1 entries) - sum(x)
+      Sb[p] = 2.0 * tot[K + 1 + p] - n_elems;   // 1^T B
+      G[p][p] = n_elems;
+#pragma unroll
+      for (int q = p + 1; q < K; ++q) {
+        G[p][q] = G[q][p] = n_elems - 2.0 * tot[2 * K + 1 + pi];
+        ++pi;
+      }
     }
   }
-  double b[8];
-  for (int p = 0; p < k; ++p) b[p] = h[p];
   bool singular = false;
-  for (int col = 0; col < k && !singular; ++col) {
-    int piv = col;
-    double best = fabs(G[col][col]);
-    for (int r = col + 1; r < k; ++r)
-      if (fabs(G[r][col]) > best) { best = fabs(G[r][col]); piv = r; }
-    if (best < 1e-9 * n_elems) { singular = true; break; }
-    if (piv != col) {
-      for (int c = 0; c < k; ++c) { const double tmp = G[col][c]; G[col][c] = G[piv][c]; G[piv][c] = tmp; }
-      const double tb = b[col]; b[col] = b[piv]; b[piv] = tb;
+#pragma unroll
+  for (int col = 0; col < K; ++col) {
+    // bring the largest |entry| of the column to the diagonal (compare-and-swap keeps the
+    // indices static, so the system stays in registers)
+#pragma unroll
+    for (int r = col + 1; r < K; ++r) {
+      if (fabs(G[r][col]) > fabs(G[col][col])) {
+#pragma unroll
+        for (int c = 0; c < K; ++c) { const double tmp = G[col][c]; G[col][c] = G[r][c]; G[r][c] = tmp; }
+        const double tb_ = b[col]; b[col] = b[r]; b[r] = tb_;
+      }
     }
-    for (int r = col + 1; r < k; ++r) {
-      const double fct = G[r][col] / G[col][col];
-      for (int c = col; c < k; ++c) G[r][c] -= fct * G[col][c];
-      b[r] -= fct * b[col];
+    if (fabs(G[col][col]) < 1e-9 * n_elems) singular = true;
+    if (!singular) {
+#pragma unroll
+      for (int r = col + 1; r < K; ++r) {
+        const double fct = G[r][col] / G[col][col];
+#pragma unroll
+        for (int c = col; c < K; ++c) G[r][c] -= fct * G[col][c];
+        b[r] -= fct * b[col];
+      }
     }
   }
-  if (singular) {
-    for (int p = 0; p < k; ++p) cur[p] = a_prev[p];
-  } else {
-    for (int r = k - 1; r >= 0; --r) {
-      double acc = b[r];
-      for (int c = r + 1; c < k; ++c) acc -= G[r][c] * cur[c];
-      cur[r] = acc / G[r][r];
-    }
+#pragma unroll
+  for (int r = K - 1; r >= 0; --r) {
+    double acc = b[r];
+#pragma unroll
+    for (int c = r + 1; c < K; ++c) acc -= G[r][c] * cur[c];
+    cur[r] = singular ? a_prev[r] : acc / G[r][r];
   }
   double beta = (1.0 + t) / (10.0 + t);
   if (beta > 0.9) beta = 0.9;
   double dot = 0.0;
-  for (int p = 0; p < k; ++p) {
-    const float a_t = float(beta * a_prev[p] + (1.0 - beta) * cur[p]);
+#pragma unroll
+  for (int p = 0; p < K; ++p) {
+    const float a_t = float(beta * a_prev[p] + (1.0 - beta) * (singular ? a_prev[p] : cur[p]));
     header[p] = a_t;
     dot += double(a_t) * Sb[p];
   }
-  header[k] = float((dot - Sx) / n_elems);
+  header[K] = float((dot - Sx) / n_elems);
 }
 
 // ====================================================================== decode (D1 + D2)
@@ -501,7 +686,7 @@ MPlan make_mplan(const accept_desc& d) {
   p.nstat = nstat_of(d.bits);
   // records of the encode kernel (stat-major, kEncodeGridMax wide at most) and, for the
   // residue initialisation, kInitGrid partial sums: both fit the same area
-  size_t bytes = size_t(nstat_of(8)) * kEncodeGridMax * sizeof(double);
+  size_t bytes = size_t(nstat_of(8)) * 2048 * sizeof(double);
   p.bytes = (bytes + 255) / 256 * 256;
   return p;
 }
@@ -523,8 +708,18 @@ hipError_t launch_mbq_compress(const accept_desc& d, const MPlan& p, const void*
   }
   if (e != hipSuccess) return e;
   mark(tm, s);
-  hipLaunchKernelGGL(mbq_finalize_kernel, dim3(1), dim3(kBlock), 0, s, partials, p.grid, d.bits, alpha_prev,
-                     double(d.n) * double(d.m), double(d.t), static_cast<float*>(header));
+  const double n_elems = double(d.n) * double(d.m);
+  float* hdr = static_cast<float*>(header);
+#define ACCEPT_FIN(KK)                                                                                         \
+  case KK:                                                                                                     \
+    hipLaunchKernelGGL(mbq_finalize_kernel<KK>, dim3(1), dim3(kBlock), 0, s, partials, p.grid, alpha_prev, \
+                       n_elems, double(d.t), hdr);                                                             \
+    break;
+  switch (d.bits) {
+    ACCEPT_FIN(1) ACCEPT_FIN(2) ACCEPT_FIN(3) ACCEPT_FIN(4) ACCEPT_FIN(5) ACCEPT_FIN(6) ACCEPT_FIN(7) ACCEPT_FIN(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef ACCEPT_FIN
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   mark(tm, s);

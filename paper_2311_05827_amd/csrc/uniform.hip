@@ -16,9 +16,20 @@ namespace {
 
 constexpr float kTinyRange = 0x1p-100f;     // smaller ranges count as an all-zero tensor
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to integer, half to even
-constexpr int kRangeGridMax = 1024;         // partial maxima of the per-tensor range pass
-constexpr int kQuantGridMax = 2048;         // workgroups of the quantize+pack kernel
-constexpr int kDequantGridMax = 8192;
+// Launch-shape constants; the -D overrides exist for tuning sweeps only.
+#ifndef ACCEPT_RANGE_GRID
+#define ACCEPT_RANGE_GRID 512
+#endif
+#ifndef ACCEPT_QUANT_GRID
+#define ACCEPT_QUANT_GRID 2048
+#endif
+#ifndef ACCEPT_DEQUANT_GRID
+#define ACCEPT_DEQUANT_GRID 8192
+#endif
+constexpr int kRangeGridMax = ACCEPT_RANGE_GRID;     // partial maxima of the per-tensor range pass
+constexpr int kQuantGridMax = ACCEPT_QUANT_GRID;     // workgroups of the quantize+pack kernel
+constexpr int kDequantGridMax = ACCEPT_DEQUANT_GRID;
+static_assert(kRangeGridMax <= 4096, "the workspace holds at most 4096 partial maxima");
 
 // s = c / L and r = L / c as correctly rounded float32 quotients (a float64 quotient of two
 // float32 values rounds to the same float32 as the exact quotient).
@@ -570,7 +581,7 @@ UPlan make_uplan(const accept_desc& d) {
     int64_t blocks = (nvec + int64_t(kBlock) * 4 - 1) / (int64_t(kBlock) * 4);
     if (blocks < 1) blocks = 1;
     p.range_grid = int(blocks < kRangeGridMax ? blocks : kRangeGridMax);
-    partial_bytes = size_t(kRangeGridMax) * sizeof(float);
+    partial_bytes = size_t(4096) * sizeof(float);
   } else if (p.seg_len % p.vec == 0 && p.seg_len >= 512) {
     p.mode = U_SEGMENTED;
     p.fast = true;
