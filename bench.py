@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sweep", action="store_true", help="also time every (config, scheme, k) cell; table on stderr")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain device copies of the benchmark tensor's size (205,520,896 B read + "
+                         "as many written per copy): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (the codec has no multi-GPU path); use --gpus 1")
@@ -106,6 +109,17 @@ def main():
     dev = torch.device("cuda:0")
     n, m = SHAPE[0], SHAPE[1] * SHAPE[2] * SHAPE[3]
     N = n * m
+
+    if args.copy_calibration:
+        src = torch.zeros(N, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        evict = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        for _ in range(10):
+            evict.sum()          # read-only traffic between copies: the copy's source comes from HBM
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("copy calibration: 10 copies of %d bytes" % (N * 4))
+        return
 
     t0 = time.time()
     act_np = si.make("cfg4_act")
