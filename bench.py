@@ -173,17 +173,25 @@ def main():
     step_bytes = 4 * N * 4
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # per-call rates, same rotation (cold inputs), events around K calls of one kind
-    def time_call(fn, other):
-        for j in range(5):
+    # per-call rates on cold inputs, two ways.  "ms": the two calls before the timed one are
+    # other calls of the step (they write up to 411 MB, and those dirty lines drain to HBM while
+    # the timed call runs).  "ms_clean": a read-only sweep of 1 GiB precedes the timed call, so
+    # the call's own traffic is all there is.
+    sweep_buf = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+
+    def time_call(fn, other, clean):
+        for j in range(3):
             fn(slots[j % 2]); other(slots[(j + 1) % 2])
         torch.cuda.synchronize()
         tot = 0.0
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = max(10, args.steps // 4)
+        reps = max(10, args.steps // 8)
         for j in range(reps):
-            other(slots[(j + 1) % 2])   # evicts: >= 230 MB of unrelated traffic between timed calls
-            other(slots[j % 2])
+            if clean:
+                sweep_buf.sum()
+            else:
+                other(slots[(j + 1) % 2])
+                other(slots[j % 2])
             e0.record()
             fn(slots[j % 2])
             e1.record()
@@ -200,12 +208,16 @@ def main():
     }
     breakdown = {}
     for name, (fn, other, ab) in calls.items():
-        ms = time_call(fn, other)
+        ms = time_call(fn, other, False)
+        ms_clean = time_call(fn, other, True)
         breakdown[name] = {
             "ms": round(ms, 5),
             "input_GBps": round(N * 4 / (ms * 1e-3) / 1e9, 1),
             "alg_bytes": ab,
             "alg_hbm_frac": round(ab / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "ms_clean": round(ms_clean, 5),
+            "input_GBps_clean": round(N * 4 / (ms_clean * 1e-3) / 1e9, 1),
+            "alg_hbm_frac_clean": round(ab / (ms_clean * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         }
 
     # per-kernel durations from HIP events recorded by the library around each launch

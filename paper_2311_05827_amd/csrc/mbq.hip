@@ -17,7 +17,7 @@ namespace {
 
 // Launch-shape constants; the -D overrides exist for tuning sweeps only.
 #ifndef ACCEPT_ENCODE_GRID
-#define ACCEPT_ENCODE_GRID 512
+#define ACCEPT_ENCODE_GRID 768
 #endif
 #ifndef ACCEPT_ENCODE_WAVES
 #define ACCEPT_ENCODE_WAVES 2  // wavefronts per SIMD the encode kernel is compiled for
@@ -84,7 +84,7 @@ __device__ __forceinline__ void build_levels(const float* __restrict__ alpha, fl
 }
 
 // ================================================================ encode + sums (M1..M4)
-// M2 without a per-element binary search.  The top 13 bits of a float32 (sign, exponent, four
+// M2 without a per-element binary search.  The top 12 bits of a float32 (sign, exponent, three
 // mantissa bits) name a bucket, i.e. an interval of reals.  For every bucket a table holds
 // lo = number of thresholds below the whole bucket; the element's position among the sorted
 // levels is then lo + #{c < maxcnt : x > tau[lo + c]}, where maxcnt is the largest number of
@@ -92,7 +92,7 @@ __device__ __forceinline__ void build_levels(const float* __restrict__ alpha, fl
 // with +inf.  The float compares decide; the table only says where to start, so the result is
 // exactly #{i : x > tau_i}.
 #ifndef ACCEPT_LUT_BITS
-#define ACCEPT_LUT_BITS 13
+#define ACCEPT_LUT_BITS 12
 #endif
 constexpr int kLutBits = ACCEPT_LUT_BITS;
 constexpr int kLutSize = 1 << kLutBits;
@@ -106,21 +106,24 @@ struct EncodeTables {
   uint32_t pat_sorted[P];
   float tau[2 * P];                        // P-1 thresholds, then +inf padding
   uint32_t spread[P * NW];                 // per sorted level: bit p of the sign pattern at bit 8*(p%4) of word p/4
-  uint8_t lut[kLutSize];
+  alignas(4) uint8_t lut[kLutSize];
   int maxcnt;
 };
 
-// Value-order successor of a bucket (buckets of negative values run backwards in bit order).
-__device__ __forceinline__ int bucket_next(int b) {
-  constexpr int HALF = kLutSize / 2;
-  if (b >= HALF) return (b == HALF) ? 0 : b - 1;  // negative side: towards -0, then +0
-  return b + 1;                                    // positive side (HALF-1 has no successor)
+// Smallest value of bucket b (bit patterns b << shift .. (b << shift) | low-ones); buckets of
+// negative values run backwards in bit order.
+__device__ __forceinline__ float bucket_vmin(int b) {
+  const uint32_t lo_bits = uint32_t(b) << (32 - kLutBits);
+  const uint32_t hi_bits = lo_bits | ((1u << (32 - kLutBits)) - 1u);
+  return u32_as_f32((b >> (kLutBits - 1)) ? hi_bits : lo_bits);
 }
 
 template <int K>
 __device__ __forceinline__ void build_encode_tables(const float* __restrict__ alpha_prev, EncodeTables<K>& tb) {
   using TB = EncodeTables<K>;
   constexpr int P = TB::P;
+  constexpr int PER = kLutSize / kBlock;  // consecutive buckets per thread
+  static_assert(kLutSize % (4 * kBlock) == 0, "each thread writes whole dwords of the bucket table");
   const int tid = threadIdx.x;
   if (tid == 0) tb.maxcnt = 1;
   build_levels<K>(alpha_prev, tb.lv_raw, tb.lv_sorted, tb.pat_sorted);
@@ -138,28 +141,47 @@ __device__ __forceinline__ void build_encode_tables(const float* __restrict__ al
     }
   }
   __syncthreads();
-  // lo(b) = #{tau_i < smallest value of bucket b}: tau[0..P-1) is sorted and tau[P-1] = +inf, so a
-  // branch-free binary search over P entries does it
-#pragma unroll 8
-  for (int b = tid; b < kLutSize; b += kBlock) {
-    const uint32_t lo_bits = uint32_t(b) << (32 - kLutBits);
-    const uint32_t hi_bits = lo_bits | ((1u << (32 - kLutBits)) - 1u);
-    const bool neg = (b >> (kLutBits - 1)) != 0;
-    const float vmin = u32_as_f32(neg ? hi_bits : lo_bits);
-    int lo = 0;
+  // lo(b) = #{tau_i < smallest value of bucket b}.  tau[0..P-1) is sorted and tau[P-1] = +inf, so a
+  // branch-free binary search over P entries finds it.  A thread owns PER consecutive buckets
+  // (one more is evaluated for the count below) and writes them four to a dword.
+  // Thresholds inside bucket b = lo(value-order successor of b) - lo(b); the successor is b+1 on
+  // the positive side and b-1 on the negative side (bucket kLutSize/2 is followed by bucket 0).
+  // Buckets of NaN bit patterns get lo = 0, which makes their differences <= 0: ignored.
+  const int b0 = tid * PER;
+  int lo[PER + 2];  // lo[j+1] belongs to bucket b0 + j; lo[0] and lo[PER+1] are the neighbours
 #pragma unroll
-    for (int s = P >> 1; s >= 1; s >>= 1) lo += (tb.tau[lo + s - 1] < vmin) ? s : 0;
-    tb.lut[b] = uint8_t(lo);
+  for (int j = -1; j <= PER; ++j) {
+    int b = b0 + j;
+    if (b < 0) b = kLutSize / 2;          // predecessor of bucket 0 in value order is -0's bucket
+    if (b >= kLutSize) b = kLutSize - 1;  // no bucket beyond the last: reuse it (difference 0)
+    const float vmin = bucket_vmin(b);
+    int l = 0;
+#pragma unroll
+    for (int s = P >> 1; s >= 1; s >>= 1) l += (tb.tau[l + s - 1] < vmin) ? s : 0;
+    lo[j + 1] = l;
   }
-  __syncthreads();
-  // thresholds inside bucket b = lo(successor) - lo(b); the top positive bucket (NaN patterns)
-  // holds none.  Buckets of NaN patterns have lo = 0 and are skipped as successors.
   int mymax = 0;
-  for (int b = tid; b < kLutSize; b += kBlock) {
-    if (b == kLutSize / 2 - 1) continue;
-    const int cnt = int(tb.lut[bucket_next(b)]) - int(tb.lut[b]);
+  const bool neg = b0 >= kLutSize / 2;
+#pragma unroll
+  for (int j = 0; j < PER; ++j) {
+    // positive side: successor is the next bucket; negative side: the previous one, except that
+    // the -0 bucket (kLutSize/2) is followed by bucket 0, whose lo the thread of bucket 0 holds;
+    // that one pair is covered from the positive side below
+    int cnt = neg ? lo[j] - lo[j + 1] : lo[j + 2] - lo[j + 1];
+    if (neg && b0 + j == kLutSize / 2) cnt = 0;
+    if (!neg && b0 + j == kLutSize / 2 - 1) cnt = 0;  // top positive bucket: NaN patterns, no successor
     mymax = cnt > mymax ? cnt : mymax;
   }
+  if (tid == 0) {
+    // thresholds inside the -0 bucket: lo(bucket 0) - lo(bucket kLutSize/2); lo[0] is that bucket
+    const int cnt = lo[1] - lo[0];
+    mymax = cnt > mymax ? cnt : mymax;
+  }
+  uint32_t* lut32 = reinterpret_cast<uint32_t*>(tb.lut);
+#pragma unroll
+  for (int j = 0; j < PER; j += 4)
+    lut32[(b0 + j) / 4] = uint32_t(lo[j + 1]) | (uint32_t(lo[j + 2]) << 8) | (uint32_t(lo[j + 3]) << 16) |
+                          (uint32_t(lo[j + 4]) << 24);
   if (mymax > 1) atomicMax(&tb.maxcnt, mymax);
   __syncthreads();
 }
@@ -278,15 +300,24 @@ __device__ __forceinline__ void encode_item_plain(const EncodeTables<K>& tb, con
   for (int c = 0; c < VEC; ++c)
 #pragma unroll
     for (int w = 0; w < NW; ++w) acc[c][w] = 0;
+  float f[8][VEC];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {  // all row loads first, so that they overlap
+    if (r < nrows) {
+      load_row<T, VEC>(xc + r * m, f[r]);
+    } else {
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) f[r][c] = 0.0f;
+    }
+  }
+#pragma unroll
   for (int r = 0; r < 8; ++r) {
-    float f[VEC];
-    if (r < nrows) load_row<T, VEC>(xc + r * m, f);
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
       uint32_t sp[NW];
 #pragma unroll
       for (int w = 0; w < NW; ++w) sp[w] = 0;
-      if (r < nrows) encode_elem<K, false>(tb, f[c], maxcnt, sp, h32, sx32);
+      if (r < nrows) encode_elem<K, false>(tb, f[r][c], maxcnt, sp, h32, sx32);
       // M3: row r of the group lands at bit 7-r of each plane byte; missing rows give 0 bits
 #pragma unroll
       for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[w];
@@ -320,9 +351,12 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
   pos.g = it / ipg;
   pos.jv = it - pos.g * ipg;
 
+  // Whole rounds (every thread of the grid has an item) go through the pipelined loop; what is
+  // left of the complete row groups is then spread over the grid one column at a time, so that
+  // no thread carries a whole extra item while the others idle.
+  const int64_t rounds = items_full / stride;
   float f[8][VEC];
-  bool have = it < items_full;
-  if (have) {
+  if (rounds > 0) {
     const T* xc = x + pos.g * 8 * m + pos.jv * VEC;
 #pragma unroll
     for (int r = 0; r < 8; ++r) load_row<T, VEC>(xc + r * m, f[r]);
@@ -338,12 +372,12 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
 #pragma unroll
   for (int i = 0; i < (NPAIR > 0 ? NPAIR : 1); ++i) st.dis[i] = 0;
 
+  const int64_t gtid = int64_t(blockIdx.x) * kBlock + tid;
   if (maxcnt == 1) {
-    while (have) {
-      const int64_t nit = it + stride;
+    for (int64_t rd = 0; rd < rounds; ++rd) {
       ItemPos npos = pos;
       item_advance(npos, step, ipg);
-      const bool nhave = nit < items_full;
+      const bool nhave = rd + 1 < rounds;
       const T* nxc = x + npos.g * 8 * m + npos.jv * VEC;
       uint32_t acc[VEC][NW];
       float h32[K];
@@ -369,16 +403,24 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
         if ((r + 1) % ACCEPT_ENCODE_SCHED_ROWS == 0) __builtin_amdgcn_sched_barrier(0);
       }
       finish_item<K, VEC>(acc, h32, sx32, payload + ((pos.g * m + pos.jv * VEC) * K), st);
-      it = nit;
       pos = npos;
-      have = nhave;
+    }
+    const int64_t first_left = rounds * stride;
+    for (int64_t s = gtid; s < (items_full - first_left) * VEC; s += stride) {
+      const int64_t item = first_left + s / VEC;
+      const int64_t g = item / ipg;
+      const int64_t j = (item - g * ipg) * VEC + s % VEC;
+      encode_item_plain<T, K, 1>(tb, x, payload, n, m, g, j, 1, st);
     }
   } else {
     for (; it < items_full; it += stride, item_advance(pos, step, ipg))
       encode_item_plain<T, K, VEC>(tb, x, payload, n, m, pos.g, pos.jv, maxcnt, st);
   }
-  for (int64_t jv = int64_t(blockIdx.x) * kBlock + tid; jv < items - items_full; jv += stride)
-    encode_item_plain<T, K, VEC>(tb, x, payload, n, m, n / 8, jv, maxcnt, st);
+  // the last, partial row group (n % 8 != 0), one column per thread
+  if (n % 8 != 0) {
+    for (int64_t j = gtid; j < m; j += stride)
+      encode_item_plain<T, K, 1>(tb, x, payload, n, m, n / 8, j, maxcnt, st);
+  }
 
   // M4: workgroup totals in a fixed order -> one record per workgroup, stat-major
   double sv[NSTAT];
