@@ -92,18 +92,86 @@ hipError_t launch_mbq_init(const accept_desc& d, const MPlan& p, const void* x, 
 __device__ __forceinline__ float u32_as_f32(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f32_as_u32(float f) { return __float_as_uint(f); }
 
-// 16-byte vector load widened to float32.
-__device__ __forceinline__ void load_vec(const float* p, float (&f)[4]) {
-  const float4 v = *reinterpret_cast<const float4*>(p);
-  f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u_t __attribute__((ext_vector_type(4)));
+
+// Cache policy.  Tensors here are far larger than the caches and each byte is used once per
+// kernel.  Streaming (non-temporal) stores let output lines drain to HBM while the kernel that
+// wrote them still runs, instead of sitting dirty in L2 / the memory-side cache and stealing
+// bandwidth from the next kernel; streaming loads keep single-use input from evicting them.
+// The -D switches exist for tuning sweeps only.
+#ifndef ACCEPT_NT_STORE
+#define ACCEPT_NT_STORE 1
+#endif
+#ifndef ACCEPT_NT_LOAD
+#define ACCEPT_NT_LOAD 1
+#endif
+
+__device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+#if ACCEPT_NT_LOAD
+  const v4u_t v = __builtin_nontemporal_load(reinterpret_cast<const v4u_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+#else
+  return load16(p);
+#endif
 }
-__device__ __forceinline__ void load_vec(const bf16_t* p, float (&f)[8]) {
-  const uint4 v = *reinterpret_cast<const uint4*>(p);
+__device__ __forceinline__ void store16_stream(void* p, uint4 v) {
+#if ACCEPT_NT_STORE
+  const v4u_t u = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(u, reinterpret_cast<v4u_t*>(p));
+#else
+  *reinterpret_cast<uint4*>(p) = v;
+#endif
+}
+
+// NDW consecutive dwords, aligned to 16 bytes when NDW % 4 == 0, to 8 when NDW % 2 == 0, else 4.
+#ifndef ACCEPT_PAYLOAD_STREAM
+#define ACCEPT_PAYLOAD_STREAM 0
+#endif
+typedef uint32_t v2u_t __attribute__((ext_vector_type(2)));
+template <int NDW>
+__device__ __forceinline__ void store_dwords(uint32_t* p, const uint32_t (&v)[NDW]) {
+#if ACCEPT_PAYLOAD_STREAM
+  if constexpr (NDW % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < NDW; i += 4) {
+      const v4u_t u = {v[i], v[i + 1], v[i + 2], v[i + 3]};
+      __builtin_nontemporal_store(u, reinterpret_cast<v4u_t*>(p + i));
+    }
+  } else if constexpr (NDW % 2 == 0) {
+#pragma unroll
+    for (int i = 0; i < NDW; i += 2) {
+      const v2u_t u = {v[i], v[i + 1]};
+      __builtin_nontemporal_store(u, reinterpret_cast<v2u_t*>(p + i));
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < NDW; ++i) __builtin_nontemporal_store(v[i], p + i);
+  }
+#else
+  struct alignas((NDW % 4 == 0) ? 16 : (NDW % 2 == 0) ? 8 : 4) Block { uint32_t w[NDW]; };
+  Block b;
+#pragma unroll
+  for (int i = 0; i < NDW; ++i) b.w[i] = v[i];
+  *reinterpret_cast<Block*>(p) = b;
+#endif
+}
+
+__device__ __forceinline__ void widen(const uint4 v, float (&f)[4]) {
+  f[0] = u32_as_f32(v.x); f[1] = u32_as_f32(v.y); f[2] = u32_as_f32(v.z); f[3] = u32_as_f32(v.w);
+}
+__device__ __forceinline__ void widen(const uint4 v, float (&f)[8]) {  // eight bfloat16, element 0 in the low half
   f[0] = u32_as_f32(v.x << 16); f[1] = u32_as_f32(v.x & 0xFFFF0000u);
   f[2] = u32_as_f32(v.y << 16); f[3] = u32_as_f32(v.y & 0xFFFF0000u);
   f[4] = u32_as_f32(v.z << 16); f[5] = u32_as_f32(v.z & 0xFFFF0000u);
   f[6] = u32_as_f32(v.w << 16); f[7] = u32_as_f32(v.w & 0xFFFF0000u);
 }
+// 16-byte vector load widened to float32; the _stream form is for data read once.
+__device__ __forceinline__ void load_vec(const float* p, float (&f)[4]) { widen(load16(p), f); }
+__device__ __forceinline__ void load_vec(const bf16_t* p, float (&f)[8]) { widen(load16(p), f); }
+__device__ __forceinline__ void load_vec_stream(const float* p, float (&f)[4]) { widen(load16_stream(p), f); }
+__device__ __forceinline__ void load_vec_stream(const bf16_t* p, float (&f)[8]) { widen(load16_stream(p), f); }
 __device__ __forceinline__ float load_one(const float* p) { return *p; }
 __device__ __forceinline__ float load_one(const bf16_t* p) { return u32_as_f32(uint32_t(p->bits) << 16); }
 
@@ -112,8 +180,9 @@ __device__ __forceinline__ uint32_t bf16_rne(float f) {
   const uint32_t b = f32_as_u32(f);
   return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
 }
+// 16-byte vector store of decompressed values (streaming).
 __device__ __forceinline__ void store_vec(float* p, const float (&f)[4]) {
-  *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
+  store16_stream(p, make_uint4(f32_as_u32(f[0]), f32_as_u32(f[1]), f32_as_u32(f[2]), f32_as_u32(f[3])));
 }
 __device__ __forceinline__ void store_vec(bf16_t* p, const float (&f)[8]) {
   uint4 v;
@@ -121,7 +190,7 @@ __device__ __forceinline__ void store_vec(bf16_t* p, const float (&f)[8]) {
   v.y = bf16_rne(f[2]) | (bf16_rne(f[3]) << 16);
   v.z = bf16_rne(f[4]) | (bf16_rne(f[5]) << 16);
   v.w = bf16_rne(f[6]) | (bf16_rne(f[7]) << 16);
-  *reinterpret_cast<uint4*>(p) = v;
+  store16_stream(p, v);
 }
 __device__ __forceinline__ void store_one(float* p, float f) { *p = f; }
 __device__ __forceinline__ void store_one(bf16_t* p, float f) { p->bits = uint16_t(bf16_rne(f)); }

@@ -248,22 +248,22 @@ __device__ __forceinline__ void finish_item(const uint32_t (&acc)[VEC][(K + 3) /
   }
   // payload: byte ((g*m + j)*K + p); the item's VEC*K bytes are contiguous
   if constexpr (VEC > 1) {
-    Dwords<NDW> out;
+    uint32_t out[NDW];
     if constexpr (K == 4) {
 #pragma unroll
-      for (int c = 0; c < VEC; ++c) out.v[c] = acc[c][0];
+      for (int c = 0; c < VEC; ++c) out[c] = acc[c][0];
     } else {
 #pragma unroll
-      for (int w = 0; w < NDW; ++w) out.v[w] = 0;
+      for (int w = 0; w < NDW; ++w) out[w] = 0;
 #pragma unroll
       for (int c = 0; c < VEC; ++c)
 #pragma unroll
         for (int p = 0; p < K; ++p) {
           const int b = c * K + p;
-          out.v[b / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (b % 4));
+          out[b / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (b % 4));
         }
     }
-    *reinterpret_cast<Dwords<NDW>*>(dst) = out;
+    store_dwords<NDW>(reinterpret_cast<uint32_t*>(dst), out);
   } else {
 #pragma unroll
     for (int p = 0; p < K; ++p) dst[p] = uint8_t(acc[0][p / 4] >> (8 * (p % 4)));
@@ -276,7 +276,7 @@ __device__ __forceinline__ void finish_item(const uint32_t (&acc)[VEC][(K + 3) /
 template <typename T, int VEC>
 __device__ __forceinline__ void load_row(const T* p, float (&f)[VEC]) {
   if constexpr (VEC > 1) {
-    load_vec(p, f);
+    load_vec_stream(p, f);  // every element of x is read once
   } else {
     f[0] = load_one(p);
   }

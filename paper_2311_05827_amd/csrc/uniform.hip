@@ -14,6 +14,19 @@ namespace accept {
 
 namespace {
 
+#ifndef ACCEPT_RANGE_STREAM
+#define ACCEPT_RANGE_STREAM 1  // the range pass reads with streaming loads as well (measured best in the step mix)
+#endif
+
+template <typename T, int V>
+__device__ __forceinline__ void load_range(const T* p, float (&f)[V]) {
+#if ACCEPT_RANGE_STREAM
+  load_vec_stream(p, f);
+#else
+  load_vec(p, f);
+#endif
+}
+
 constexpr float kTinyRange = 0x1p-100f;     // smaller ranges count as an all-zero tensor
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to integer, half to even
 // Launch-shape constants; the -D overrides exist for tuning sweeps only.
@@ -91,7 +104,7 @@ __global__ __launch_bounds__(kBlock) void range_tensor_kernel(const T* __restric
   for (; v + (UNROLL - 1) * stride < nvec; v += UNROLL * stride) {
     float f[UNROLL][VEC];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) load_vec(x + (v + u * stride) * VEC, f[u]);
+    for (int u = 0; u < UNROLL; ++u) load_range<T, VEC>(x + (v + u * stride) * VEC, f[u]);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
@@ -99,7 +112,7 @@ __global__ __launch_bounds__(kBlock) void range_tensor_kernel(const T* __restric
   }
   for (; v < nvec; v += stride) {
     float f[VEC];
-    load_vec(x + v * VEC, f);
+    load_range<T, VEC>(x + v * VEC, f);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[e]));
   }
@@ -138,7 +151,7 @@ __global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restr
     for (; j + 3 * kWave < count; j += 4 * kWave) {
       float f[4][VEC];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) load_vec(base + (j + u * kWave) * VEC, f[u]);
+      for (int u = 0; u < 4; ++u) load_range<T, VEC>(base + (j + u * kWave) * VEC, f[u]);
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -146,7 +159,7 @@ __global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restr
     }
     for (; j < count; j += kWave) {
       float f[VEC];
-      load_vec(base + j * VEC, f);
+      load_range<T, VEC>(base + j * VEC, f);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[e]));
     }
@@ -242,11 +255,6 @@ __device__ __forceinline__ void pack8(const uint32_t (&P)[8], uint32_t (&out)[K]
   }
 }
 
-template <int K>
-struct alignas((K % 4 == 0) ? 16 : (K % 2 == 0) ? 8 : 4) Dwords {
-  uint32_t v[K];
-};
-
 // Slow path for one group of 8 elements -> k bytes (tails and odd channel geometries):
 // scalar loads, per-byte stores guarded by the payload size.  Elements at or beyond N
 // contribute zero bits.
@@ -311,7 +319,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     const T* xt = x + tile * kTileElems;
     float f[LOADS][VEC];
 #pragma unroll
-    for (int u = 0; u < LOADS; ++u) load_vec(xt + (u * kBlock + tid) * VEC, f[u]);
+    for (int u = 0; u < LOADS; ++u) load_vec_stream(xt + (u * kBlock + tid) * VEC, f[u]);
     ChanPos pos = tile_pos;
 #pragma unroll
     for (int u = 0; u < LOADS; ++u) {
@@ -330,9 +338,9 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     const uint4 a = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid]);
     const uint4 b = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid + 4]);
     const uint32_t P[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    Dwords<K> out;
-    pack8<K>(P, out.v);
-    *reinterpret_cast<Dwords<K>*>(payload32 + (tile * kBlock + tid) * K) = out;
+    uint32_t out[K];
+    pack8<K>(P, out);
+    store_dwords<K>(payload32 + (tile * kBlock + tid) * K, out);
   }
 
   // Everything the tile loop did not cover, 8 elements (k bytes) per thread.
