@@ -322,10 +322,10 @@ def cpu_baseline(np, act_np, grad_np, n, m):
 def sweep(A, torch, si, np):
     """Cold-input timings of every (config, scheme, k, dtype, range mode) cell; stderr table."""
     dev = torch.device("cuda:0")
-    scratch = torch.empty(160 * 1024 * 1024, dtype=torch.float32, device=dev)  # 640 MB cache flusher
+    scratch = torch.zeros(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB, read-only sweep between calls
 
     def flush():
-        scratch.add_(1.0)
+        scratch.sum()
 
     def timeit(fn, reps=20):
         fn(); torch.cuda.synchronize()

@@ -367,9 +367,17 @@ __device__ __forceinline__ void dequant4(const uint32_t* __restrict__ payload32,
   const int64_t bit = e0 * K;
   const int64_t w0 = bit >> 5;
   const int sh = int(bit & 31);
-  const uint32_t hi = __builtin_bswap32(payload32[w0]);
-  uint32_t lo = 0;
-  if ((32 % W != 0) && sh + W > 32) lo = __builtin_bswap32(payload32[w0 + 1]);
+  uint32_t hi, lo = 0;
+  if (32 % W != 0) {
+    // fields may straddle two dwords: always fetch the pair as one 8-byte load (the vector path
+    // stops one 32-element group before the end, so dword w0+1 always exists)
+    struct alignas(4) Pair { uint32_t a, b; };
+    const Pair pr = *reinterpret_cast<const Pair*>(payload32 + w0);
+    hi = __builtin_bswap32(pr.a);
+    lo = __builtin_bswap32(pr.b);
+  } else {
+    hi = __builtin_bswap32(payload32[w0]);
+  }
   const uint64_t win = (uint64_t(hi) << 32) | lo;
   uint32_t piece = uint32_t(win >> (64 - W - sh));
   // Offset binary -> two's complement: flip the top bit of each k-bit field (k < 8).
@@ -533,7 +541,9 @@ hipError_t launch_dequant(const accept_desc& d, const float* header, const uint3
   // The vector path covers whole groups of 32 elements (k whole dwords), so that no dword
   // load reaches past the payload; per channel it also needs vectors that stay in a segment.
   const bool fast = !PERCH || (seg_len % VEC == 0);
-  const int64_t fast_vecs = fast ? (N / 32) * (32 / VEC) : 0;
+  // widths whose 4-code fields straddle dwords read dword pairs: keep one group in reserve
+  const int64_t groups32 = (32 % (4 * K) != 0) ? (N / 32 > 0 ? N / 32 - 1 : 0) : N / 32;
+  const int64_t fast_vecs = fast ? groups32 * (32 / VEC) : 0;
   const int64_t work = fast_vecs > (N - fast_vecs * VEC) ? fast_vecs : (N - fast_vecs * VEC);
   int64_t blocks = (work + kBlock - 1) / kBlock;
   if (blocks < 1) blocks = 1;
