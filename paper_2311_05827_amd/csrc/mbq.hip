@@ -106,6 +106,10 @@ struct EncodeTables {
   uint32_t pat_sorted[P];
   float tau[2 * P];                        // P-1 thresholds, then +inf padding
   uint32_t spread[P * NW];                 // per sorted level: bit p of the sign pattern at bit 8*(p%4) of word p/4
+  // k <= 4 only: row lo = {tau[lo] (or +inf), spread[lo]}, so that one 8-byte read at lo*8 and one
+  // 4-byte read at lo*8 + 12 (= spread[lo+1]) give everything an element needs
+  alignas(8) uint32_t pair[2 * (P + 1)];
+  static constexpr int LUT_SHIFT = (K <= 4) ? 3 : 0;  // bucket table entries are lo << LUT_SHIFT
   alignas(4) uint8_t lut[kLutSize];
   int maxcnt;
 };
@@ -141,47 +145,56 @@ __device__ __forceinline__ void build_encode_tables(const float* __restrict__ al
     }
   }
   __syncthreads();
+  if (K <= 4 && tid <= P) {
+    tb.pair[2 * tid] = f32_as_u32(tb.tau[tid]);                  // tau[P-1], tau[P] are +inf
+    tb.pair[2 * tid + 1] = tid < P ? tb.spread[tid] : 0u;
+  }
   // lo(b) = #{tau_i < smallest value of bucket b}.  tau[0..P-1) is sorted and tau[P-1] = +inf, so a
   // branch-free binary search over P entries finds it.  A thread owns PER consecutive buckets
   // (one more is evaluated for the count below) and writes them four to a dword.
   // Thresholds inside bucket b = lo(value-order successor of b) - lo(b); the successor is b+1 on
   // the positive side and b-1 on the negative side (bucket kLutSize/2 is followed by bucket 0).
   // Buckets of NaN bit patterns get lo = 0, which makes their differences <= 0: ignored.
-  const int b0 = tid * PER;
-  int lo[PER + 2];  // lo[j+1] belongs to bucket b0 + j; lo[0] and lo[PER+1] are the neighbours
-#pragma unroll
-  for (int j = -1; j <= PER; ++j) {
-    int b = b0 + j;
-    if (b < 0) b = kLutSize / 2;          // predecessor of bucket 0 in value order is -0's bucket
-    if (b >= kLutSize) b = kLutSize - 1;  // no bucket beyond the last: reuse it (difference 0)
-    const float vmin = bucket_vmin(b);
-    int l = 0;
-#pragma unroll
-    for (int s = P >> 1; s >= 1; s >>= 1) l += (tb.tau[l + s - 1] < vmin) ? s : 0;
-    lo[j + 1] = l;
-  }
   int mymax = 0;
-  const bool neg = b0 >= kLutSize / 2;
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    // positive side: successor is the next bucket; negative side: the previous one, except that
-    // the -0 bucket (kLutSize/2) is followed by bucket 0, whose lo the thread of bucket 0 holds;
-    // that one pair is covered from the positive side below
-    int cnt = neg ? lo[j] - lo[j + 1] : lo[j + 2] - lo[j + 1];
-    if (neg && b0 + j == kLutSize / 2) cnt = 0;
-    if (!neg && b0 + j == kLutSize / 2 - 1) cnt = 0;  // top positive bucket: NaN patterns, no successor
-    mymax = cnt > mymax ? cnt : mymax;
-  }
-  if (tid == 0) {
-    // thresholds inside the -0 bucket: lo(bucket 0) - lo(bucket kLutSize/2); lo[0] is that bucket
-    const int cnt = lo[1] - lo[0];
-    mymax = cnt > mymax ? cnt : mymax;
-  }
   uint32_t* lut32 = reinterpret_cast<uint32_t*>(tb.lut);
+  constexpr int CH = 8;  // buckets per step: bounds the registers this prologue needs
+  static_assert(PER % CH == 0, "bucket chunks");
+#pragma nounroll
+  for (int c0 = 0; c0 < PER; c0 += CH) {
+    const int b0 = tid * PER + c0;
+    const bool neg = b0 >= kLutSize / 2;
+    int lo[CH + 2];  // lo[j+1] belongs to bucket b0 + j; lo[0] and lo[CH+1] are the neighbours
 #pragma unroll
-  for (int j = 0; j < PER; j += 4)
-    lut32[(b0 + j) / 4] = uint32_t(lo[j + 1]) | (uint32_t(lo[j + 2]) << 8) | (uint32_t(lo[j + 3]) << 16) |
-                          (uint32_t(lo[j + 4]) << 24);
+    for (int j = -1; j <= CH; ++j) {
+      int b = b0 + j;
+      if (b < 0) b = kLutSize / 2;          // predecessor of bucket 0 in value order is -0's bucket
+      if (b >= kLutSize) b = kLutSize - 1;  // no bucket beyond the last: reuse it (difference 0)
+      const float vmin = bucket_vmin(b);
+      int l = 0;
+#pragma unroll
+      for (int s = P >> 1; s >= 1; s >>= 1) l += (tb.tau[l + s - 1] < vmin) ? s : 0;
+      lo[j + 1] = l;
+    }
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      // positive side: the successor is the next bucket; negative side: the previous one, except
+      // that the -0 bucket (kLutSize/2) is followed by bucket 0: that pair is counted below
+      int cnt = neg ? lo[j] - lo[j + 1] : lo[j + 2] - lo[j + 1];
+      if (neg && b0 + j == kLutSize / 2) cnt = 0;
+      if (!neg && b0 + j == kLutSize / 2 - 1) cnt = 0;  // top positive bucket: NaN patterns, no successor
+      mymax = cnt > mymax ? cnt : mymax;
+    }
+    if (b0 == 0) {
+      // thresholds inside the -0 bucket: lo(bucket 0) - lo(bucket kLutSize/2); lo[0] is that bucket
+      const int cnt = lo[1] - lo[0];
+      mymax = cnt > mymax ? cnt : mymax;
+    }
+#pragma unroll
+    for (int j = 0; j < CH; j += 4)
+      lut32[(b0 + j) / 4] = (uint32_t(lo[j + 1]) | (uint32_t(lo[j + 2]) << 8) | (uint32_t(lo[j + 3]) << 16) |
+                             (uint32_t(lo[j + 4]) << 24))
+                            << TB::LUT_SHIFT;  // lo < 32 when shifted by 3: no carry between bytes
+  }
   if (mymax > 1) atomicMax(&tb.maxcnt, mymax);
   __syncthreads();
 }
@@ -204,14 +217,23 @@ template <int K, bool ONE>
 __device__ __forceinline__ void encode_elem(const EncodeTables<K>& tb, float x, int maxcnt,
                                             uint32_t (&sp)[(K + 3) / 4], float (&a32)[K], float& sx32) {
   using TB = EncodeTables<K>;
-  const int lo = tb.lut[f32_as_u32(x) >> (32 - kLutBits)];
-  int idx = lo + ((x > tb.tau[lo]) ? 1 : 0);
-  if (!ONE) {
+  if constexpr (ONE && K <= 4) {
+    // at most one threshold per bucket: the level is lo or lo+1
+    const uint32_t off = tb.lut[f32_as_u32(x) >> (32 - kLutBits)];  // lo * 8
+    const char* row = reinterpret_cast<const char*>(tb.pair) + off;
+    const uint2 ts = *reinterpret_cast<const uint2*>(row);            // tau[lo], spread[lo]
+    const uint32_t sp_up = *reinterpret_cast<const uint32_t*>(row + 12);  // spread[lo+1]
+    sp[0] = (x > u32_as_f32(ts.x)) ? sp_up : ts.y;
+  } else {
+    const int lo = tb.lut[f32_as_u32(x) >> (32 - kLutBits)] >> TB::LUT_SHIFT;
+    int idx = lo + ((x > tb.tau[lo]) ? 1 : 0);
+    if (!ONE) {
 #pragma nounroll
-    for (int c = 1; c < maxcnt; ++c) idx += (x > tb.tau[lo + c]) ? 1 : 0;
-  }
+      for (int c = 1; c < maxcnt; ++c) idx += (x > tb.tau[lo + c]) ? 1 : 0;
+    }
 #pragma unroll
-  for (int w = 0; w < TB::NW; ++w) sp[w] = tb.spread[idx * TB::NW + w];
+    for (int w = 0; w < TB::NW; ++w) sp[w] = tb.spread[idx * TB::NW + w];
+  }
   sx32 = __fadd_rn(sx32, x);
 #pragma unroll
   for (int p = 0; p < K; ++p) a32[p] = __fmaf_rn(x, float((sp[p / 4] >> (8 * (p % 4))) & 0xFFu), a32[p]);
@@ -377,7 +399,9 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
     for (int64_t rd = 0; rd < rounds; ++rd) {
       ItemPos npos = pos;
       item_advance(npos, step, ipg);
-      const bool nhave = rd + 1 < rounds;
+      // In the last round there is no next item: re-read the current one (valid, harmless), so
+      // that the loads stay unconditional and the compiler can reuse the row registers in place.
+      if (rd + 1 >= rounds) npos = pos;
       const T* nxc = x + npos.g * 8 * m + npos.jv * VEC;
       uint32_t acc[VEC][NW];
       float h32[K];
@@ -397,7 +421,7 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
 #pragma unroll
           for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[w];
         }
-        if (nhave) load_row<T, VEC>(nxc + r * m, f[r]);
+        load_row<T, VEC>(nxc + r * m, f[r]);
         // keep the instruction scheduler from interleaving rows: it would otherwise hoist the
         // table reads of all 8*VEC elements and run out of registers
         if ((r + 1) % ACCEPT_ENCODE_SCHED_ROWS == 0) __builtin_amdgcn_sched_barrier(0);
@@ -413,8 +437,13 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
       encode_item_plain<T, K, 1>(tb, x, payload, n, m, g, j, 1, st);
     }
   } else {
-    for (; it < items_full; it += stride, item_advance(pos, step, ipg))
-      encode_item_plain<T, K, VEC>(tb, x, payload, n, m, pos.g, pos.jv, maxcnt, st);
+    // several thresholds share a bucket (levels closer than a bucket's width): rare.  One column
+    // per thread keeps this path's register needs out of the kernel's budget.
+    const int64_t cols_full = (n / 8) * m;
+    for (int64_t s = gtid; s < cols_full; s += stride) {
+      const int64_t g = s / m;
+      encode_item_plain<T, K, 1>(tb, x, payload, n, m, g, s - g * m, maxcnt, st);
+    }
   }
   // the last, partial row group (n % 8 != 0), one column per thread
   if (n % 8 != 0) {
@@ -451,22 +480,34 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
 // moving average with beta = min(0.9, (1+t)/(10+t)) and m_q = mean(B alpha_t - x);
 // header = [alpha_t, m_q].  K is a template parameter so that the k x k system lives in
 // registers.
+constexpr int kFinBlock = kBlock;
+constexpr int kFinRPT = (kEncodeGridMax + kFinBlock - 1) / kFinBlock;  // records per thread, at most
 template <int K>
-__global__ __launch_bounds__(kBlock) void mbq_finalize_kernel(const double* __restrict__ partials, int nrec,
+__global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* __restrict__ partials, int nrec,
                                                                const float* __restrict__ alpha_prev, double n_elems,
                                                                double t, float* __restrict__ header) {
   constexpr int NSTAT = nstat_of(K);
   __shared__ double tot[NSTAT];
   const int tid = threadIdx.x;
-  // every thread sums records tid, tid+256, ... of every statistic (all loads independent, so
-  // they overlap), then a fixed butterfly per wavefront and a fixed order across wavefronts
-  __shared__ double red[kBlock / kWave][NSTAT];
+  // every thread takes records tid, tid+256, ... (at most kFinRPT) of every statistic; the loads
+  // of a statistic are all issued before their adds, so few memory latencies are paid.  Then a
+  // fixed butterfly per wavefront and a fixed order across wavefronts: the totals do not depend
+  // on timing.
+  __shared__ double red[kFinBlock / kWave][NSTAT];
   double a[NSTAT];
+  double v[NSTAT][kFinRPT];
 #pragma unroll
-  for (int s = 0; s < NSTAT; ++s) a[s] = 0.0;
-  for (int b = tid; b < nrec; b += kBlock) {
+  for (int s = 0; s < NSTAT; ++s)
 #pragma unroll
-    for (int s = 0; s < NSTAT; ++s) a[s] += partials[int64_t(s) * nrec + b];
+    for (int i = 0; i < kFinRPT; ++i) {
+      const int b = tid + i * kFinBlock;
+      v[s][i] = (b < nrec) ? partials[int64_t(s) * nrec + b] : 0.0;
+    }
+#pragma unroll
+  for (int s = 0; s < NSTAT; ++s) {
+    a[s] = v[s][0];
+#pragma unroll
+    for (int i = 1; i < kFinRPT; ++i) a[s] += v[s][i];
   }
 #pragma unroll
   for (int s = 0; s < NSTAT; ++s) {
@@ -477,7 +518,7 @@ __global__ __launch_bounds__(kBlock) void mbq_finalize_kernel(const double* __re
   if (tid < NSTAT) {
     double v = red[0][tid];
 #pragma unroll
-    for (int w = 1; w < kBlock / kWave; ++w) v += red[w][tid];
+    for (int w = 1; w < kFinBlock / kWave; ++w) v += red[w][tid];
     tot[tid] = v;
   }
   __syncthreads();
@@ -754,7 +795,7 @@ hipError_t launch_mbq_compress(const accept_desc& d, const MPlan& p, const void*
   float* hdr = static_cast<float*>(header);
 #define ACCEPT_FIN(KK)                                                                                         \
   case KK:                                                                                                     \
-    hipLaunchKernelGGL(mbq_finalize_kernel<KK>, dim3(1), dim3(kBlock), 0, s, partials, p.grid, alpha_prev, \
+    hipLaunchKernelGGL(mbq_finalize_kernel<KK>, dim3(1), dim3(kFinBlock), 0, s, partials, p.grid, alpha_prev, \
                        n_elems, double(d.t), hdr);                                                             \
     break;
   switch (d.bits) {
