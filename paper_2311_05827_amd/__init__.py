@@ -16,6 +16,8 @@ _BINDING_NAMES = (
 
 
 def __getattr__(name):
+    if name == "boundary":
+        return importlib.import_module(__name__ + ".boundary")
     if name == "binding" or name in _BINDING_NAMES:
         mod = importlib.import_module(__name__ + ".binding")
         return mod if name == "binding" else getattr(mod, name)
