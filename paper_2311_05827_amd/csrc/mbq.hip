@@ -399,9 +399,10 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
     for (int64_t rd = 0; rd < rounds; ++rd) {
       ItemPos npos = pos;
       item_advance(npos, step, ipg);
-      // In the last round there is no next item: re-read the current one (valid, harmless), so
-      // that the loads stay unconditional and the compiler can reuse the row registers in place.
-      if (rd + 1 >= rounds) npos = pos;
+      // In the last round there is no next item: every lane then re-reads the first item of the
+      // tensor (valid, one cache line per row for the whole wavefront), so that the loads stay
+      // unconditional and the compiler can reuse the row registers in place.
+      if (rd + 1 >= rounds) { npos.g = 0; npos.jv = 0; }
       const T* nxc = x + npos.g * 8 * m + npos.jv * VEC;
       uint32_t acc[VEC][NW];
       float h32[K];
@@ -541,6 +542,7 @@ __global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* _
     }
   }
   bool singular = false;
+  double inv[K];
 #pragma unroll
   for (int col = 0; col < K; ++col) {
     // bring the largest |entry| of the column to the diagonal (compare-and-swap keeps the
@@ -554,10 +556,11 @@ __global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* _
       }
     }
     if (fabs(G[col][col]) < 1e-9 * n_elems) singular = true;
+    inv[col] = 1.0 / G[col][col];  // one division per column; its products differ from quotients by an ulp
     if (!singular) {
 #pragma unroll
       for (int r = col + 1; r < K; ++r) {
-        const double fct = G[r][col] / G[col][col];
+        const double fct = G[r][col] * inv[col];
 #pragma unroll
         for (int c = col; c < K; ++c) G[r][c] -= fct * G[col][c];
         b[r] -= fct * b[col];
@@ -569,7 +572,7 @@ __global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* _
     double acc = b[r];
 #pragma unroll
     for (int c = r + 1; c < K; ++c) acc -= G[r][c] * cur[c];
-    cur[r] = singular ? a_prev[r] : acc / G[r][r];
+    cur[r] = singular ? a_prev[r] : acc * inv[r];
   }
   double beta = (1.0 + t) / (10.0 + t);
   if (beta > 0.9) beta = 0.9;
