@@ -89,6 +89,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--sweep", action="store_true", help="also time every (config, scheme, k) cell; table on stderr")
+    ap.add_argument("--sweep-json", default=None, help="with --sweep: also write the table to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--graph", action="store_true",
                     help="replay a captured HIP graph of two steps instead of launching every call eagerly "
@@ -286,7 +287,7 @@ def main():
         cpu = cpu_baseline(np, act_np, grad_np, n, m)
 
     if args.sweep:
-        sweep(A, torch, si, np)
+        sweep(A, torch, si, np, args.sweep_json)
 
     out = {
         "metric": METRIC,
@@ -346,7 +347,7 @@ def cpu_baseline(np, act_np, grad_np, n, m):
     }
 
 
-def sweep(A, torch, si, np):
+def sweep(A, torch, si, np, out_path=None):
     """Cold-input timings of every (config, scheme, k, dtype, range mode) cell; stderr table."""
     dev = torch.device("cuda:0")
     scratch = torch.zeros(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB, read-only sweep between calls
@@ -413,9 +414,9 @@ def sweep(A, torch, si, np):
                 100 * cell["compress_alg_frac"], td * 1e3, cell["decompress_out_GBps"],
                 100 * cell["decompress_alg_frac"]))
         del x32, x16
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "sweep.json"), "w") as f:
-        json.dump(cells, f, indent=1)
+    if out_path:
+        with open(out_path, "w") as f:
+            json.dump(cells, f, indent=1)
 
 
 if __name__ == "__main__":
