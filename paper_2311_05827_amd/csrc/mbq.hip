@@ -8,7 +8,7 @@
 // byte, and eight shift-or steps build the k plane bytes of a column), so the encoder needs
 // no LDS exchange and its k*VEC output bytes per lane are contiguous across lanes.  The
 // least-squares sums ride along in the same pass: bit counts come from popcounts of the
-// finished plane bytes, B^T x from masked adds.
+// finished plane bytes, B^T x from multiply-adds with the 0/1 plane bits.
 #include "common.hpp"
 
 namespace accept {
