@@ -22,8 +22,8 @@ namespace {
 #ifndef ACCEPT_ENCODE_WAVES
 #define ACCEPT_ENCODE_WAVES 2  // wavefronts per SIMD the encode kernel is compiled for
 #endif
-#ifndef ACCEPT_ENCODE_SCHED_ROWS
-#define ACCEPT_ENCODE_SCHED_ROWS 2  // rows whose table lookups the scheduler may interleave
+#ifndef ACCEPT_ENCODE_GROUP
+#define ACCEPT_ENCODE_GROUP 4  // elements whose table lookups are issued together (at least one row)
 #endif
 #ifndef ACCEPT_DECODE_GRID
 #define ACCEPT_DECODE_GRID 8192
@@ -107,8 +107,9 @@ struct EncodeTables {
   float tau[2 * P];                        // P-1 thresholds, then +inf padding
   uint32_t spread[P * NW];                 // per sorted level: bit p of the sign pattern at bit 8*(p%4) of word p/4
   // k <= 4 only: row lo = {tau[lo] (or +inf), spread[lo]}, so that one 8-byte read at lo*8 and one
-  // 4-byte read at lo*8 + 12 (= spread[lo+1]) give everything an element needs
-  alignas(8) uint32_t pair[2 * (P + 1)];
+  // 4-byte read at lo*8 + 12 (= spread[lo+1]) give everything an element needs (two 8-byte reads
+  // and one 4-byte read when a bucket may hold two thresholds)
+  alignas(8) uint32_t pair[2 * (P + 2)];
   static constexpr int LUT_SHIFT = (K <= 4) ? 3 : 0;  // bucket table entries are lo << LUT_SHIFT
   alignas(4) uint8_t lut[kLutSize];
   int maxcnt;
@@ -145,8 +146,8 @@ __device__ __forceinline__ void build_encode_tables(const float* __restrict__ al
     }
   }
   __syncthreads();
-  if (K <= 4 && tid <= P) {
-    tb.pair[2 * tid] = f32_as_u32(tb.tau[tid]);                  // tau[P-1], tau[P] are +inf
+  if (K <= 4 && tid <= P + 1) {
+    tb.pair[2 * tid] = f32_as_u32(tb.tau[tid]);                  // tau[P-1], tau[P], tau[P+1] are +inf
     tb.pair[2 * tid + 1] = tid < P ? tb.spread[tid] : 0u;
   }
   // lo(b) = #{tau_i < smallest value of bucket b}.  tau[0..P-1) is sorted and tau[P-1] = +inf, so a
@@ -209,34 +210,68 @@ struct EncodeStats {
   uint32_t dis[NPAIR > 0 ? NPAIR : 1];  // elements whose planes p<q disagree
 };
 
-// M2 for one element: sorted-level position via the bucket table, then the level's spread
+// M2 for one element, any K: sorted-level position via the bucket table, then the level's spread
 // sign pattern.  Adds x to the running float32 sums: S_x always, A_p where plane p is +1
 // (byte p of the spread word is 0 or 1; converting it to float and using a fused
 // multiply-add gives x*1 or x*0 exactly, so each step rounds like a plain add).
-template <int K, bool ONE>
-__device__ __forceinline__ void encode_elem(const EncodeTables<K>& tb, float x, int maxcnt,
-                                            uint32_t (&sp)[(K + 3) / 4], float (&a32)[K], float& sx32) {
-  using TB = EncodeTables<K>;
-  if constexpr (ONE && K <= 4) {
-    // at most one threshold per bucket: the level is lo or lo+1
-    const uint32_t off = tb.lut[f32_as_u32(x) >> (32 - kLutBits)];  // lo * 8
-    const char* row = reinterpret_cast<const char*>(tb.pair) + off;
-    const uint2 ts = *reinterpret_cast<const uint2*>(row);            // tau[lo], spread[lo]
-    const uint32_t sp_up = *reinterpret_cast<const uint32_t*>(row + 12);  // spread[lo+1]
-    sp[0] = (x > u32_as_f32(ts.x)) ? sp_up : ts.y;
-  } else {
-    const int lo = tb.lut[f32_as_u32(x) >> (32 - kLutBits)] >> TB::LUT_SHIFT;
-    int idx = lo + ((x > tb.tau[lo]) ? 1 : 0);
-    if (!ONE) {
-#pragma nounroll
-      for (int c = 1; c < maxcnt; ++c) idx += (x > tb.tau[lo + c]) ? 1 : 0;
-    }
-#pragma unroll
-    for (int w = 0; w < TB::NW; ++w) sp[w] = tb.spread[idx * TB::NW + w];
-  }
+template <int K>
+__device__ __forceinline__ void accumulate_elem(float x, const uint32_t (&sp)[(K + 3) / 4], float (&a32)[K],
+                                                float& sx32) {
   sx32 = __fadd_rn(sx32, x);
 #pragma unroll
   for (int p = 0; p < K; ++p) a32[p] = __fmaf_rn(x, float((sp[p / 4] >> (8 * (p % 4))) & 0xFFu), a32[p]);
+}
+
+template <int K>
+__device__ __forceinline__ void encode_elem(const EncodeTables<K>& tb, float x, int maxcnt,
+                                            uint32_t (&sp)[(K + 3) / 4], float (&a32)[K], float& sx32) {
+  using TB = EncodeTables<K>;
+  const int lo = tb.lut[f32_as_u32(x) >> (32 - kLutBits)] >> TB::LUT_SHIFT;
+  int idx = lo + ((x > tb.tau[lo]) ? 1 : 0);
+#pragma nounroll
+  for (int c = 1; c < maxcnt; ++c) idx += (x > tb.tau[lo + c]) ? 1 : 0;
+#pragma unroll
+  for (int w = 0; w < TB::NW; ++w) sp[w] = tb.spread[idx * TB::NW + w];
+  accumulate_elem<K>(x, sp, a32, sx32);
+}
+
+// M2 for NE elements.  MC = 1 or 2: no bucket holds more than MC thresholds (K <= 4 then takes
+// everything an element needs from the pair table: the level is lo .. lo+MC); MC = 0: any
+// number, maxcnt.  The pair-table form is written in three passes over the elements (bucket
+// reads, row reads, selects and sums), so that the local-memory latencies of the NE elements
+// overlap whatever order the instruction scheduler keeps.
+template <int K, int MC, int NE>
+__device__ __forceinline__ void encode_group(const EncodeTables<K>& tb, const float (&xs)[NE], int maxcnt,
+                                             uint32_t (&sp)[NE][(K + 3) / 4], float (&a32)[K], float& sx32) {
+  if constexpr (K <= 4 && (MC == 1 || MC == 2)) {
+    const char* pair = reinterpret_cast<const char*>(tb.pair);
+    uint32_t off[NE];  // lo * 8
+#pragma unroll
+    for (int e = 0; e < NE; ++e) off[e] = tb.lut[f32_as_u32(xs[e]) >> (32 - kLutBits)];
+    uint2 t0[NE], t1[NE];  // {tau[lo], spread[lo]}, {tau[lo+1], spread[lo+1]}
+    uint32_t top[NE];      // spread[lo+MC]
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      const char* row = pair + off[e];
+      t0[e] = *reinterpret_cast<const uint2*>(row);
+      if constexpr (MC == 2) t1[e] = *reinterpret_cast<const uint2*>(row + 8);
+      top[e] = *reinterpret_cast<const uint32_t*>(row + 8 * MC + 4);
+    }
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      const float x = xs[e];
+      if constexpr (MC == 1) {
+        sp[e][0] = (x > u32_as_f32(t0[e].x)) ? top[e] : t0[e].y;
+      } else {  // tau[lo] <= tau[lo+1]
+        const uint32_t s01 = (x > u32_as_f32(t0[e].x)) ? t1[e].y : t0[e].y;
+        sp[e][0] = (x > u32_as_f32(t1[e].x)) ? top[e] : s01;
+      }
+      accumulate_elem<K>(x, sp[e], a32, sx32);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < NE; ++e) encode_elem<K>(tb, xs[e], MC == 1 ? 1 : maxcnt, sp[e], a32, sx32);
+  }
 }
 
 // End of an item: bit counts from the finished plane bytes, payload store, float32 partial
@@ -295,71 +330,145 @@ __device__ __forceinline__ void finish_item(const uint32_t (&acc)[VEC][(K + 3) /
   for (int p = 0; p < K; ++p) st.H[p] += double(h32[p]);
 }
 
+// One row's share of an item as it comes from memory: VEC elements in a 16-byte vector, or a
+// single element's bits.  Rows are kept in this form while they wait and widened to float32
+// only when they are used, so that a load's result is not needed before then.
+template <int VEC>
+struct RawRow {
+  uint4 v;
+};
+template <>
+struct RawRow<1> {
+  uint32_t v;
+};
 template <typename T, int VEC>
-__device__ __forceinline__ void load_row(const T* p, float (&f)[VEC]) {
+__device__ __forceinline__ RawRow<VEC> load_raw(const T* p) {
+  RawRow<VEC> r;
   if constexpr (VEC > 1) {
-    load_vec_stream(p, f);  // every element of x is read once
+    r.v = load16_stream(p);  // every element of x is read once
+  } else if constexpr (sizeof(T) == 4) {
+    r.v = f32_as_u32(*reinterpret_cast<const float*>(p));
   } else {
-    f[0] = load_one(p);
+    r.v = uint32_t(*reinterpret_cast<const uint16_t*>(p)) << 16;
+  }
+  return r;
+}
+template <int VEC>
+__device__ __forceinline__ void widen_raw(const RawRow<VEC>& r, float (&f)[VEC]) {
+  if constexpr (VEC > 1) {
+    widen(r.v, f);
+  } else {
+    f[0] = u32_as_f32(r.v);
   }
 }
 
-// Plain (not pipelined) item: any number of valid rows, any maxcnt.
-template <typename T, int K, int VEC>
-__device__ __forceinline__ void encode_item_plain(const EncodeTables<K>& tb, const T* __restrict__ x,
-                                                  uint8_t* __restrict__ payload, int64_t n, int64_t m, int64_t g,
-                                                  int64_t jv, int maxcnt, EncodeStats<K>& st) {
+// Plain (not pipelined) item of one column: any number of valid rows.
+template <typename T, int K, int MC>
+__device__ __forceinline__ void encode_column(const EncodeTables<K>& tb, const T* __restrict__ x,
+                                              uint8_t* __restrict__ payload, int64_t n, int64_t m, int64_t g,
+                                              int64_t j, int maxcnt, EncodeStats<K>& st) {
   constexpr int NW = (K + 3) / 4;
   const int64_t row0 = g * 8;
   const int nrows = (n - row0) < 8 ? int(n - row0) : 8;
-  const T* xc = x + row0 * m + jv * VEC;
-  uint32_t acc[VEC][NW];
+  const T* xc = x + row0 * m + j;
+  float xs[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {  // all row loads first, so that they overlap
+    RawRow<1> raw;
+    raw.v = 0u;
+    if (r < nrows) raw = load_raw<T, 1>(xc + r * m);
+    float one[1];
+    widen_raw<1>(raw, one);
+    xs[r] = one[0];  // a missing row reads as +0: it adds nothing to the sums
+  }
   float h32[K];
   float sx32 = 0.0f;
 #pragma unroll
   for (int p = 0; p < K; ++p) h32[p] = 0.0f;
+  uint32_t sp[8][NW];
+  encode_group<K, MC, 8>(tb, xs, maxcnt, sp, h32, sx32);
+  // M3: row r of the group lands at bit 7-r of each plane byte; missing rows give 0 bits
+  uint32_t acc[1][NW];
 #pragma unroll
-  for (int c = 0; c < VEC; ++c)
+  for (int w = 0; w < NW; ++w) acc[0][w] = 0;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) acc[c][w] = 0;
-  float f[8][VEC];
+  for (int r = 0; r < 8; ++r)
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {  // all row loads first, so that they overlap
-    if (r < nrows) {
-      load_row<T, VEC>(xc + r * m, f[r]);
-    } else {
+    for (int w = 0; w < NW; ++w) acc[0][w] = (acc[0][w] << 1) | (r < nrows ? sp[r][w] : 0u);
+  finish_item<K, 1>(acc, h32, sx32, payload + ((g * m + j) * K), st);
+}
+
+// The pipelined loop over whole rounds of the grid (every thread has an item in every round).
+template <typename T, int K, int VEC, int MC>
+__device__ __forceinline__ void encode_rounds(const EncodeTables<K>& tb, const T* __restrict__ x,
+                                              uint8_t* __restrict__ payload, int64_t m, int64_t ipg, int64_t rounds,
+                                              ItemPos pos, const ItemStep& step, RawRow<VEC> (&fr)[8],
+                                              EncodeStats<K>& st) {
+  constexpr int NW = (K + 3) / 4;
+  constexpr int GR = VEC >= ACCEPT_ENCODE_GROUP ? 1 : ACCEPT_ENCODE_GROUP / VEC;  // rows handled together
+  // The first item's rows have had the whole table build to arrive.  Waiting for them here
+  // (vmcnt 0, the other counters untouched) gives the loop an empty set of outstanding loads
+  // on entry whatever code precedes it, so that the waits the compiler places inside the loop
+  // are the ones its own steady state needs and no more.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  for (int64_t rd = 0; rd < rounds; ++rd) {
+    ItemPos npos = pos;
+    item_advance(npos, step, ipg);
+    // In the last round there is no next item: every lane then re-reads the first item of the
+    // tensor (valid, one cache line per row for the whole wavefront), so that the loads stay
+    // unconditional and the compiler can reuse the row registers in place.
+    if (rd + 1 >= rounds) { npos.g = 0; npos.jv = 0; }
+    const T* nxc = x + npos.g * 8 * m + npos.jv * VEC;
+    uint32_t acc[VEC][NW];
+    float h32[K];
+    float sx32 = 0.0f;
 #pragma unroll
-      for (int c = 0; c < VEC; ++c) f[r][c] = 0.0f;
+    for (int p = 0; p < K; ++p) h32[p] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c)
+#pragma unroll
+      for (int w = 0; w < NW; ++w) acc[c][w] = 0;
+#pragma unroll
+    for (int r0 = 0; r0 < 8; r0 += GR) {
+      float xs[GR * VEC];
+#pragma unroll
+      for (int rr = 0; rr < GR; ++rr) {
+        float row[VEC];
+        widen_raw<VEC>(fr[r0 + rr], row);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) xs[rr * VEC + c] = row[c];
+      }
+      uint32_t sp[GR * VEC][NW];
+      encode_group<K, MC, GR * VEC>(tb, xs, MC, sp, h32, sx32);
+      // M3: row r of the group lands at bit 7-r of each plane byte
+#pragma unroll
+      for (int rr = 0; rr < GR; ++rr)
+#pragma unroll
+        for (int c = 0; c < VEC; ++c)
+#pragma unroll
+          for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[rr * VEC + c][w];
+#pragma unroll
+      for (int rr = 0; rr < GR; ++rr) fr[r0 + rr] = load_raw<T, VEC>(nxc + (r0 + rr) * m);
+      // keep the instruction scheduler from mixing groups: it would otherwise hoist the table
+      // reads of all 8*VEC elements and run out of registers
+      __builtin_amdgcn_sched_barrier(0);
     }
+    finish_item<K, VEC>(acc, h32, sx32, payload + ((pos.g * m + pos.jv * VEC) * K), st);
+    pos = npos;
   }
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
-#pragma unroll
-    for (int c = 0; c < VEC; ++c) {
-      uint32_t sp[NW];
-#pragma unroll
-      for (int w = 0; w < NW; ++w) sp[w] = 0;
-      if (r < nrows) encode_elem<K, false>(tb, f[r][c], maxcnt, sp, h32, sx32);
-      // M3: row r of the group lands at bit 7-r of each plane byte; missing rows give 0 bits
-#pragma unroll
-      for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[w];
-    }
-  }
-  finish_item<K, VEC>(acc, h32, sx32, payload + ((g * m + jv * VEC) * K), st);
 }
 
 // Fused M1..M4.  Items whose eight rows all exist run through a software-pipelined loop:
 // row r of the next item is requested as soon as row r of the current item has been
 // consumed, so a wavefront always has loads in flight while it works; the first item's rows
 // are requested before the tables are built.  The last, partial row group (n % 8 != 0) and
-// the rare case of several thresholds per bucket take the plain path.
+// the rare case of more than two thresholds per bucket take the plain path.
 template <typename T, int K, int VEC>
 __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel(const T* __restrict__ x,
                                                              const float* __restrict__ alpha_prev,
                                                              uint8_t* __restrict__ payload,
                                                              double* __restrict__ partials, int64_t n, int64_t m,
                                                              int64_t ipg, int64_t items, ItemStep step) {
-  constexpr int NW = (K + 3) / 4;
   constexpr int NPAIR = K * (K - 1) / 2;
   constexpr int NSTAT = nstat_of(K);
   __shared__ EncodeTables<K> tb;
@@ -377,15 +486,17 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
   // left of the complete row groups is then spread over the grid one column at a time, so that
   // no thread carries a whole extra item while the others idle.
   const int64_t rounds = items_full / stride;
-  float f[8][VEC];
+  RawRow<VEC> fr[8];
   if (rounds > 0) {
     const T* xc = x + pos.g * 8 * m + pos.jv * VEC;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) load_row<T, VEC>(xc + r * m, f[r]);
+    for (int r = 0; r < 8; ++r) fr[r] = load_raw<T, VEC>(xc + r * m);
   }
 
   build_encode_tables<K>(alpha_prev, tb);
-  const int maxcnt = tb.maxcnt;
+  // the same value in every lane: read it into a scalar register, so that the choice of path
+  // below is a scalar branch and not a divergent one whose sides run one after the other
+  const int maxcnt = __builtin_amdgcn_readfirstlane(tb.maxcnt);
 
   EncodeStats<K> st;
   st.Sx = 0.0;
@@ -395,47 +506,22 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
   for (int i = 0; i < (NPAIR > 0 ? NPAIR : 1); ++i) st.dis[i] = 0;
 
   const int64_t gtid = int64_t(blockIdx.x) * kBlock + tid;
+  // whole rounds pipelined, then the items of the last, incomplete round one column per thread
+  const int64_t first_left = rounds * stride;
+  const int64_t cols_left = (items_full - first_left) * VEC;
   if (maxcnt == 1) {
-    for (int64_t rd = 0; rd < rounds; ++rd) {
-      ItemPos npos = pos;
-      item_advance(npos, step, ipg);
-      // In the last round there is no next item: every lane then re-reads the first item of the
-      // tensor (valid, one cache line per row for the whole wavefront), so that the loads stay
-      // unconditional and the compiler can reuse the row registers in place.
-      if (rd + 1 >= rounds) { npos.g = 0; npos.jv = 0; }
-      const T* nxc = x + npos.g * 8 * m + npos.jv * VEC;
-      uint32_t acc[VEC][NW];
-      float h32[K];
-      float sx32 = 0.0f;
-#pragma unroll
-      for (int p = 0; p < K; ++p) h32[p] = 0.0f;
-#pragma unroll
-      for (int c = 0; c < VEC; ++c)
-#pragma unroll
-        for (int w = 0; w < NW; ++w) acc[c][w] = 0;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-#pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-          uint32_t sp[NW];
-          encode_elem<K, true>(tb, f[r][c], 1, sp, h32, sx32);
-#pragma unroll
-          for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[w];
-        }
-        load_row<T, VEC>(nxc + r * m, f[r]);
-        // keep the instruction scheduler from interleaving rows: it would otherwise hoist the
-        // table reads of all 8*VEC elements and run out of registers
-        if ((r + 1) % ACCEPT_ENCODE_SCHED_ROWS == 0) __builtin_amdgcn_sched_barrier(0);
-      }
-      finish_item<K, VEC>(acc, h32, sx32, payload + ((pos.g * m + pos.jv * VEC) * K), st);
-      pos = npos;
-    }
-    const int64_t first_left = rounds * stride;
-    for (int64_t s = gtid; s < (items_full - first_left) * VEC; s += stride) {
+    encode_rounds<T, K, VEC, 1>(tb, x, payload, m, ipg, rounds, pos, step, fr, st);
+    for (int64_t s = gtid; s < cols_left; s += stride) {
       const int64_t item = first_left + s / VEC;
       const int64_t g = item / ipg;
-      const int64_t j = (item - g * ipg) * VEC + s % VEC;
-      encode_item_plain<T, K, 1>(tb, x, payload, n, m, g, j, 1, st);
+      encode_column<T, K, 1>(tb, x, payload, n, m, g, (item - g * ipg) * VEC + s % VEC, 1, st);
+    }
+  } else if (maxcnt == 2 && K <= 4) {
+    encode_rounds<T, K, VEC, 2>(tb, x, payload, m, ipg, rounds, pos, step, fr, st);
+    for (int64_t s = gtid; s < cols_left; s += stride) {
+      const int64_t item = first_left + s / VEC;
+      const int64_t g = item / ipg;
+      encode_column<T, K, 2>(tb, x, payload, n, m, g, (item - g * ipg) * VEC + s % VEC, 2, st);
     }
   } else {
     // several thresholds share a bucket (levels closer than a bucket's width): rare.  One column
@@ -443,13 +529,13 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
     const int64_t cols_full = (n / 8) * m;
     for (int64_t s = gtid; s < cols_full; s += stride) {
       const int64_t g = s / m;
-      encode_item_plain<T, K, 1>(tb, x, payload, n, m, g, s - g * m, maxcnt, st);
+      encode_column<T, K, 0>(tb, x, payload, n, m, g, s - g * m, maxcnt, st);
     }
   }
   // the last, partial row group (n % 8 != 0), one column per thread
   if (n % 8 != 0) {
     for (int64_t j = gtid; j < m; j += stride)
-      encode_item_plain<T, K, 1>(tb, x, payload, n, m, n / 8, j, maxcnt, st);
+      encode_column<T, K, 0>(tb, x, payload, n, m, n / 8, j, maxcnt, st);
   }
 
   // M4: workgroup totals in a fixed order -> one record per workgroup, stat-major

@@ -132,6 +132,22 @@ def test_singular_gram_and_special_values(A):
     run_case(A, x, 2, 8, 36, alpha_prev=a, tag="thresholds+denormals")
 
 
+@pytest.mark.parametrize("k,alpha", [(3, [1.0, 0.03, 0.02]), (4, [1.0, 0.5, 0.03, 0.02]), (4, [0.6, 0.58, 0.3, 0.29])])
+def test_two_thresholds_per_bucket(A, k, alpha):
+    """Levels closer than the width of a bucket of the level search's float-prefix table: the
+    encoder then compares against two thresholds per element.  The shapes give whole pipelined
+    rounds, a last incomplete round and a ragged last row group; values sit on and next to the
+    thresholds as well."""
+    a = np.asarray(alpha, np.float32)
+    _, _, tau = orc.mbq_levels(a)
+    for n, m, bf in [(8, 8 * 1024 * 100 + 4 * 37, False), (19, 400004, False), (16, 800008, True), (5, 1003, False)]:
+        x = si.make_shape("student_t3", (n, m), 7100 + n)
+        x = (x * np.float32(0.8 / x.std())).astype(np.float32)
+        edge = np.concatenate([tau, np.nextafter(tau, np.float32(np.inf)), np.nextafter(tau, np.float32(-np.inf))])
+        x.reshape(-1)[: edge.size * 5 : 5] = edge.astype(np.float32)
+        run_case(A, x, k, n, m, alpha_prev=a, in_bf16=bf, tag="two-per-bucket")
+
+
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
 def test_residue_init(A, k):
     torch = torch_mod()
