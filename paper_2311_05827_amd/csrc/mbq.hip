@@ -200,6 +200,53 @@ __device__ __forceinline__ void build_encode_tables(const float* __restrict__ al
   __syncthreads();
 }
 
+// Sum of NS per-thread float64 values over the 256 threads of a workgroup, in a fixed order
+// (so the result does not depend on timing): the values go to local memory one statistic per
+// row, 16 threads per statistic add 16 consecutive entries each, one thread adds those 16
+// partial sums.  Far cheaper than NS butterflies of 64-bit lane exchanges.  buf holds
+// kStatChunk rows; more statistics than that take several passes.  On return thread s < NS
+// holds total s in its return value (other threads: unspecified).
+constexpr int kStatChunk = 16;
+struct StatScratch {
+  double v[kStatChunk][kBlock];
+  double part[kStatChunk][16];
+};
+template <int NS>
+__device__ __forceinline__ double block_sum_stats(const double (&sv)[NS], StatScratch& buf) {
+  static_assert(kBlock == 256, "16 threads x 16 entries per statistic");
+  const int tid = threadIdx.x;
+  double mine = 0.0;
+#pragma unroll
+  for (int c0 = 0; c0 < NS; c0 += kStatChunk) {
+    constexpr int kAll = kStatChunk;
+    const int nc = (NS - c0) < kAll ? (NS - c0) : kAll;
+    if (c0 > 0) __syncthreads();  // the previous pass has been read
+#pragma unroll
+    for (int s = 0; s < kAll; ++s)
+      if (c0 + s < NS) buf.v[s][tid] = sv[c0 + s];
+    __syncthreads();
+    {
+      const int s = tid >> 4, part = tid & 15;
+      if (s < nc) {
+        const double* src = &buf.v[s][part * 16];
+        double a = src[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) a += src[i];
+        buf.part[s][part] = a;
+      }
+    }
+    __syncthreads();
+    if (tid >= c0 && tid < c0 + nc) {
+      const double* src = buf.part[tid - c0];
+      double a = src[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) a += src[i];
+      mine = a;
+    }
+  }
+  return mine;
+}
+
 // Statistics carried by one thread.
 template <int K>
 struct EncodeStats {
@@ -472,7 +519,7 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
   constexpr int NPAIR = K * (K - 1) / 2;
   constexpr int NSTAT = nstat_of(K);
   __shared__ EncodeTables<K> tb;
-  __shared__ double red[kBlock / kWave][NSTAT];
+  __shared__ StatScratch red;
 
   const int tid = threadIdx.x;
   const int64_t stride = int64_t(gridDim.x) * kBlock;
@@ -547,18 +594,8 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
   for (int p = 0; p < K; ++p) sv[K + 1 + p] = double(st.cnt[p]);
 #pragma unroll
   for (int i = 0; i < NPAIR; ++i) sv[2 * K + 1 + i] = double(st.dis[i]);
-#pragma unroll
-  for (int s = 0; s < NSTAT; ++s) {
-    const double w = wave_sum(sv[s]);
-    if ((tid & (kWave - 1)) == 0) red[tid / kWave][s] = w;
-  }
-  __syncthreads();
-  if (tid < NSTAT) {
-    double t = red[0][tid];
-#pragma unroll
-    for (int w = 1; w < kBlock / kWave; ++w) t += red[w][tid];
-    partials[int64_t(tid) * gridDim.x + blockIdx.x] = t;
-  }
+  const double total = block_sum_stats<NSTAT>(sv, red);
+  if (tid < NSTAT) partials[int64_t(tid) * gridDim.x + blockIdx.x] = total;
 }
 
 // ========================================================================= finalize (M5)
@@ -577,10 +614,9 @@ __global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* _
   __shared__ double tot[NSTAT];
   const int tid = threadIdx.x;
   // every thread takes records tid, tid+256, ... (at most kFinRPT) of every statistic; the loads
-  // of a statistic are all issued before their adds, so few memory latencies are paid.  Then a
-  // fixed butterfly per wavefront and a fixed order across wavefronts: the totals do not depend
-  // on timing.
-  __shared__ double red[kFinBlock / kWave][NSTAT];
+  // of a statistic are all issued before their adds, so few memory latencies are paid.  Then
+  // the fixed-order workgroup sum: the totals do not depend on timing.
+  __shared__ StatScratch red;
   double a[NSTAT];
   double v[NSTAT][kFinRPT];
 #pragma unroll
@@ -596,18 +632,8 @@ __global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* _
 #pragma unroll
     for (int i = 1; i < kFinRPT; ++i) a[s] += v[s][i];
   }
-#pragma unroll
-  for (int s = 0; s < NSTAT; ++s) {
-    const double w = wave_sum(a[s]);
-    if ((tid & (kWave - 1)) == 0) red[tid / kWave][s] = w;
-  }
-  __syncthreads();
-  if (tid < NSTAT) {
-    double v = red[0][tid];
-#pragma unroll
-    for (int w = 1; w < kFinBlock / kWave; ++w) v += red[w][tid];
-    tot[tid] = v;
-  }
+  const double total = block_sum_stats<NSTAT>(a, red);
+  if (tid < NSTAT) tot[tid] = total;
   __syncthreads();
   if (tid != 0) return;
   double G[K][K], b[K], Sb[K], a_prev[K], cur[K];
