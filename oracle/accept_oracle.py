@@ -25,7 +25,8 @@ and the size table's payload column, beta's printed formula, the bit-width sched
 printed averages, numpy.packbits as an independent packer, brute force over tiny
 tensors, closed forms for k=1, normal-equation and mean-preservation invariants.
 Unpinned by the paper (documented readings only): the order in which scheme U lays
-codes into bytes for k other than 4 and 8, and which two elements share a byte at k=4.
+codes into bytes for k other than 4 and 8, and which two elements share a byte at k=4
+(flat neighbours in the packed layout, batch neighbours in LAYOUT_BATCH).
 """
 from __future__ import annotations
 
@@ -34,24 +35,41 @@ import numpy as np
 F32 = np.float32
 SCHEME_UNIFORM = 0
 SCHEME_MBQ = 1
+# payload layouts: this library's packed forms (dense stream / bit planes); the paper's own
+# backward layout (codes of 8/k consecutive batch entries share a byte); one byte per value,
+# the paper's "w/o enc." rows
+LAYOUT_PACKED = 0
+LAYOUT_BATCH = 1
+LAYOUT_UNENCODED = 2
 TINY_RANGE = F32(2.0 ** -100)  # ranges below this are treated as an all-zero tensor
 
 
 # --------------------------------------------------------------------------------------
 # sizes, schedules (section "Transmission Data Comparison"; bit-width paragraphs)
 # --------------------------------------------------------------------------------------
-def packed_size(scheme, bits, n, m, channels=0):
+def packed_size(scheme, bits, n, m, channels=0, layout=LAYOUT_PACKED):
     """(header_bytes, payload_bytes) of one compressed tensor.
 
     Scheme M: alpha (k floats) + mean error (1 float); payload ceil(n/8)*m*k bytes
     (eq. (compress ratio) and the sentence before it).  Scheme U: one 32-bit scale (one
     per channel in the per-channel extension); payload ceil(n*m*k/8) bytes ("n/(8/k) x w
     x h x c" bytes in the paper, where 8/k is an integer).
+
+    LAYOUT_BATCH (scheme U, k in 2, 4, 8): ceil(n/(8/k)) * m bytes, the paper's own count.
+    LAYOUT_UNENCODED (the "w/o enc." rows of the size table): one byte per transmitted
+    integer, i.e. n*m bytes for scheme U and n*m*k for scheme M.
     """
     n, m, k = int(n), int(m), int(bits)
     if scheme == SCHEME_MBQ:
-        return 4 * (k + 1), ((n + 7) // 8) * m * k
+        assert layout in (LAYOUT_PACKED, LAYOUT_UNENCODED)
+        return 4 * (k + 1), (n * m * k if layout == LAYOUT_UNENCODED else ((n + 7) // 8) * m * k)
     c = max(int(channels), 1)
+    if layout == LAYOUT_UNENCODED:
+        return 4 * c, n * m
+    if layout == LAYOUT_BATCH:
+        assert 8 % k == 0
+        per = 8 // k
+        return 4 * c, ((n + per - 1) // per) * m
     return 4 * c, (n * m * k + 7) // 8
 
 
@@ -204,7 +222,39 @@ def unpack_stream(payload, k, N):
     return codes.reshape(-1)[:N].copy()
 
 
-def uniform_compress(x, k, n, m, channels=0, in_bf16=False, rounding=0, seed=0):
+def pack_batch(u, k, n, m):
+    """The paper's own backward layout ("Backward Encoder": the shifted codes of two
+    tensors along the first dimension are combined into one at k = 4, so that g_c has
+    n/2 x w x h x c bytes): byte (g, j) holds the codes of batch entries g*(8/k) ..
+    g*(8/k) + 8/k - 1 of column j, first entry in the most significant bits, like the
+    forward encoder's worked example.  k must divide 8; entries beyond n contribute 0
+    bits.  Which entries pair up is a reading: the paper does not say."""
+    n, m = int(n), int(m)
+    assert 8 % k == 0
+    per = 8 // k
+    G = (n + per - 1) // per
+    pad = np.zeros((G * per, m), dtype=np.uint64)
+    pad[:n] = np.asarray(u, dtype=np.uint64).reshape(n, m)
+    pad = pad.reshape(G, per, m)
+    out = np.zeros((G, m), dtype=np.uint64)
+    for i in range(per):
+        out |= pad[:, i, :] << np.uint64(k * (per - 1 - i))
+    return out.astype(np.uint8).reshape(-1)
+
+
+def unpack_batch(payload, k, n, m):
+    """Inverse of pack_batch."""
+    n, m = int(n), int(m)
+    per = 8 // k
+    G = (n + per - 1) // per
+    pl = np.asarray(payload, dtype=np.uint8).reshape(G, m).astype(np.uint64)
+    u = np.zeros((G, per, m), dtype=np.uint64)
+    for i in range(per):
+        u[:, i, :] = (pl >> np.uint64(k * (per - 1 - i))) & np.uint64(2 ** k - 1)
+    return u.reshape(G * per, m)[:n].reshape(-1)
+
+
+def uniform_compress(x, k, n, m, channels=0, in_bf16=False, rounding=0, seed=0, layout=LAYOUT_PACKED):
     """(g, k) -> (s, g_c): header bytes (little-endian float32 scale per range group) and
     payload bytes."""
     assert 2 <= k <= 8
@@ -212,23 +262,33 @@ def uniform_compress(x, k, n, m, channels=0, in_bf16=False, rounding=0, seed=0):
     c = uniform_range(x32, n, m, channels)
     s, r = uniform_scale(c, k)
     q = uniform_quantize(x32, r, k, n, m, rounding, seed)
-    payload = pack_stream(uniform_codes(q, k), k)
+    if layout == LAYOUT_UNENCODED:  # g_q itself, one two's-complement byte per value
+        payload = (np.asarray(q, dtype=np.int64) & 0xFF).astype(np.uint8)
+    elif layout == LAYOUT_BATCH:
+        payload = pack_batch(uniform_codes(q, k), k, n, m)
+    else:
+        payload = pack_stream(uniform_codes(q, k), k)
     return s.astype("<f4").tobytes(), payload
 
 
-def uniform_decode(payload, k, N):
+def uniform_decode(payload, k, N, layout=LAYOUT_PACKED, n=None, m=None):
     """g_q from g_c ("Backward Decoder": subtract the offset; skipped at k = 8)."""
-    u = unpack_stream(payload, k, N).astype(np.int64)
+    if layout == LAYOUT_UNENCODED:
+        return np.asarray(payload, dtype=np.uint8).reshape(-1)[:N].view(np.int8).astype(np.int32)
+    if layout == LAYOUT_BATCH:
+        u = unpack_batch(payload, k, n, m).astype(np.int64)
+    else:
+        u = unpack_stream(payload, k, N).astype(np.int64)
     if k == 8:
         return np.where(u >= 128, u - 256, u).astype(np.int32)
     return (u - 2 ** (k - 1)).astype(np.int32)
 
 
-def uniform_decompress(header, payload, k, n, m, channels=0, out_bf16=False):
+def uniform_decompress(header, payload, k, n, m, channels=0, out_bf16=False, layout=LAYOUT_PACKED):
     """g_hat = g_q * s ("Backward Dequantizer"), one float32 multiply per element."""
     N = int(n) * int(m)
     s = np.frombuffer(bytes(header), dtype="<f4").astype(F32)
-    q = uniform_decode(payload, k, N)
+    q = uniform_decode(payload, k, N, layout, n, m)
     xh = (q.astype(F32) * _per_element(s, n, m)).astype(F32)
     return narrow_bf16(xh) if out_bf16 else xh
 
@@ -301,6 +361,25 @@ def mbq_unpack(payload, k, n, m):
     return code[:n].reshape(-1)
 
 
+def mbq_pack_unencoded(code, k):
+    """The "w/o enc." form of B: every binary base as an 8-bit integer of its own, +1 or
+    -1, element-major with the k bases innermost (n*m*k bytes)."""
+    code = np.asarray(code, dtype=np.int64).reshape(-1)
+    out = np.empty((code.size, k), dtype=np.int8)
+    for p in range(k):
+        out[:, p] = np.where((code >> p) & 1, 1, -1)
+    return out.reshape(-1).view(np.uint8)
+
+
+def mbq_unpack_unencoded(payload, k, N):
+    """Sign patterns back from the +-1 bytes."""
+    b = np.asarray(payload, dtype=np.uint8).reshape(-1)[: N * k].view(np.int8).reshape(N, k)
+    code = np.zeros(N, dtype=np.int64)
+    for p in range(k):
+        code |= (b[:, p] > 0).astype(np.int64) << p
+    return code
+
+
 def mbq_stats(x, code, k):
     """float64 sums needed by eq. (alpha solution) and the bias term: G = B^T B,
     h = B^T x, S_b = 1^T B, S_x = 1^T x, with b = +1 where the pattern bit is 1."""
@@ -359,12 +438,12 @@ def mbq_mean_error(alpha_t, Sb, Sx, n_elems):
     return F32((np.dot(a, Sb) - Sx) / n_elems)
 
 
-def mbq_compress(x, k, n, m, alpha_prev, t, in_bf16=False):
+def mbq_compress(x, k, n, m, alpha_prev, t, in_bf16=False, layout=LAYOUT_PACKED):
     """(x, k, alpha_(t-1)) -> header [alpha_t (k floats), m_q] and payload B_c."""
     x32 = _as_f32(x, in_bf16)
     N = int(n) * int(m)
     code = mbq_assign(x32, alpha_prev)
-    payload = mbq_pack(code, k, n, m)
+    payload = mbq_pack_unencoded(code, k) if layout == LAYOUT_UNENCODED else mbq_pack(code, k, n, m)
     G, h, Sb, Sx = mbq_stats(x32, code, k)
     alpha_t, _ = mbq_alpha_update(alpha_prev, G, h, t, N)
     mq = mbq_mean_error(alpha_t, Sb, Sx, N)
@@ -372,12 +451,15 @@ def mbq_compress(x, k, n, m, alpha_prev, t, in_bf16=False):
     return header, payload
 
 
-def mbq_decompress(header, payload, k, n, m, out_bf16=False):
+def mbq_decompress(header, payload, k, n, m, out_bf16=False, layout=LAYOUT_PACKED):
     """"Forward Dequantizer": x_hat = B alpha - m_q.  The product is the float32 sum of
     +-alpha_p in the order p = 0..k-1 starting from 0, then one float32 subtraction."""
     hdr = np.frombuffer(bytes(header), dtype="<f4").astype(F32)
     alpha, mq = hdr[:k], hdr[k]
-    code = mbq_unpack(payload, k, n, m)
+    if layout == LAYOUT_UNENCODED:
+        code = mbq_unpack_unencoded(payload, k, int(n) * int(m))
+    else:
+        code = mbq_unpack(payload, k, n, m)
     acc = np.zeros(code.size, dtype=F32)
     for p in range(k):
         acc = (acc + np.where((code >> p) & 1, alpha[p], -alpha[p]).astype(F32)).astype(F32)

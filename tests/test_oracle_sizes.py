@@ -29,13 +29,18 @@ def test_size_table_payload_column(golden_rows):
             hdr, pay = orc.packed_size(orc.SCHEME_UNIFORM, k, 128, N // 128)
             assert pay == N * k // 8 and hdr == 4
             assert 0.44 <= printed - pay / 1024 <= 0.56, (tensor, row, k)
+            # the paper's own count, n/(8/k) x w x h x c bytes, is the batch layout's size
+            assert orc.packed_size(orc.SCHEME_UNIFORM, k, 128, N // 128, layout=orc.LAYOUT_BATCH)[1] == pay
         elif row == "noenc":
-            # every binary base stored in a byte of its own: 8x the encoded payload
-            _, pay = orc.packed_size(orc.SCHEME_MBQ, k, 128, N // 128)
-            assert 0.9 <= printed - 8 * pay / 1024 <= 1.2, (tensor, row, k)
+            # every binary base stored in a byte of its own
+            _, pay = orc.packed_size(orc.SCHEME_MBQ, k, 128, N // 128, layout=orc.LAYOUT_UNENCODED)
+            assert pay == N * k
+            assert 0.9 <= printed - pay / 1024 <= 1.2, (tensor, row, k)
         else:
-            _, pay = orc.packed_size(orc.SCHEME_UNIFORM, k, 128, N // 128)
-            assert 0.0 <= printed - 2 * pay / 1024 <= 0.6, (tensor, row, k)
+            # every quantized gradient in a byte of its own
+            _, pay = orc.packed_size(orc.SCHEME_UNIFORM, k, 128, N // 128, layout=orc.LAYOUT_UNENCODED)
+            assert pay == N
+            assert 0.0 <= printed - pay / 1024 <= 0.6, (tensor, row, k)
 
 
 @pytest.mark.parametrize("n,m,k", [(128, 8192, 2), (128, 8192, 4), (5, 33, 3), (8, 1, 4), (9, 7, 1), (1, 1, 8)])
