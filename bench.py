@@ -372,9 +372,11 @@ def sweep(A, torch, si, np, out_path=None):
         ("cfg2_grad", [("U", 4, 0, False), ("U", 2, 0, False)]),
         ("cfg3_act", [("U", k, 0, False) for k in range(2, 9)] + [("M", k, 0, False) for k in (2, 3, 4)]),
         ("cfg4_act", [("U", k, c, b) for k in (4, 6, 8) for c in (0, 256) for b in (False, True)]
-         + [("M", k, 0, False) for k in (2, 3, 4)] + [("M", k, 0, True) for k in (2, 4)]),
+         + [("M", k, 0, False) for k in (2, 3, 4)] + [("M", k, 0, True) for k in (2, 4)]
+         + [("Mu", 4, 0, False)]),  # Mu: one byte per binary base
         ("cfg4_grad", [("U", k, c, False) for k in (4, 6, 8) for c in (0, 256)]
-         + [("Us", k, 0, False) for k in (4, 8)]),  # Us: stochastic rounding
+         + [("Us", k, 0, False) for k in (4, 8)]      # Us: stochastic rounding
+         + [("Ub", 4, 0, False), ("Uu", 4, 0, False)]),  # Ub: batch-pair layout, Uu: one byte per code
         ("cfg5_hidden", [("U", k, 0, False) for k in (3, 5, 6, 7)] + [("M", 3, 0, False)]),
         ("cfg5_grad", [("U", k, 0, False) for k in (3, 5, 6, 7)]),
     ]
@@ -389,19 +391,21 @@ def sweep(A, torch, si, np, out_path=None):
         for scheme, k, C, bf in cases:
             x = x16 if bf else x32
             b = 2 if bf else 4
-            if scheme in ("U", "Us"):
+            layout = {"b": A.LAYOUT_BATCH, "u": A.LAYOUT_UNENCODED}.get(scheme[1:], A.LAYOUT_PACKED)
+            if scheme[0] == "U":
                 d = A.make_desc(A.UNIFORM, k, n, m, channels=C, in_dtype=A.BF16 if bf else A.F32,
-                                out_dtype=A.BF16 if bf else A.F32,
+                                out_dtype=A.BF16 if bf else A.F32, layout=layout,
                                 rounding=A.ROUND_STOCHASTIC if scheme == "Us" else A.ROUND_NEAREST_EVEN, seed=7)
                 alpha = None
-                cb = alg_bytes("range", N, n, m, k, b) + alg_bytes("quantize_pack", N, n, m, k, b)
-                db = alg_bytes("unpack_dequant", N, n, m, k, b, b)
             else:
                 d = A.make_desc(A.MBQ, k, n, m, t=1, in_dtype=A.BF16 if bf else A.F32,
-                                out_dtype=A.BF16 if bf else A.F32)
+                                out_dtype=A.BF16 if bf else A.F32, layout=layout)
                 alpha = A.accept_mbq_init(d, x)
-                cb = alg_bytes("mbq_encode", N, n, m, k, b)
-                db = alg_bytes("mbq_decode", N, n, m, k, b, b)
+            # algorithmic bytes of the call: the input (twice for scheme U: range pass, quantize
+            # pass), the header and the payload of this layout one way; the same plus the output back
+            hb, pb = A.accept_packed_size(d)
+            cb = (2 if scheme[0] == "U" else 1) * N * b + hb + pb
+            db = hb + pb + N * b
             h, p, w = A.alloc_outputs(d, dev)
             out = torch.empty(N, dtype=torch.bfloat16 if bf else torch.float32, device=dev)
             tc = timeit(lambda: A.accept_compress(d, x, alpha_prev=alpha, header=h, payload=p, workspace=w))

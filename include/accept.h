@@ -53,6 +53,19 @@ typedef enum {
 enum { ACCEPT_UNIFORM = 0, ACCEPT_MBQ = 1 };      /* accept_desc.scheme                     */
 enum { ACCEPT_F32 = 0, ACCEPT_BF16 = 1 };         /* accept_desc.in_dtype / out_dtype       */
 enum { ACCEPT_ROUND_NEAREST_EVEN = 0, ACCEPT_ROUND_STOCHASTIC = 1 }; /* accept_desc.rounding */
+/* accept_desc.layout: how the integers are laid into the payload.
+ *   PACKED     the forms this library is built around: UNIFORM a dense stream of k-bit codes
+ *              in flat element order, MBQ bit planes along the batch dimension.
+ *   BATCH      UNIFORM only, k in {2, 4, 8}: the layout of the paper's "Backward Encoder",
+ *              where the shifted codes of 8/k consecutive batch entries of one column share
+ *              a byte (byte g*m + j holds rows g*(8/k) .. of column j, first row in the most
+ *              significant bits, rows >= n as 0 bits); ceil(n/(8/k))*m bytes.
+ *   UNENCODED  the "w/o enc." rows of the paper's size table: every transmitted integer in
+ *              a byte of its own.  UNIFORM: q as a two's-complement byte, n*m bytes.  MBQ:
+ *              each binary base as +1 / -1, element-major with the k bases innermost,
+ *              n*m*k bytes.
+ * BATCH and UNENCODED exist to measure what the packed layouts buy; their kernels are plain. */
+enum { ACCEPT_LAYOUT_PACKED = 0, ACCEPT_LAYOUT_BATCH = 1, ACCEPT_LAYOUT_UNENCODED = 2 };
 
 /*
  * Problem descriptor (host memory, plain data, 64 bytes).
@@ -68,6 +81,7 @@ enum { ACCEPT_ROUND_NEAREST_EVEN = 0, ACCEPT_ROUND_STOCHASTIC = 1 }; /* accept_d
  *            streams).  ACCEPT_ROUND_STOCHASTIC: the paper's rule, floor(v)+1 with
  *            probability v-floor(v); the uniform number of element i is the top 24 bits
  *            of splitmix64's output function at seed + (i+1)*0x9E3779B97F4A7C15.
+ *  layout    ACCEPT_LAYOUT_PACKED (0) unless one of the comparison layouts is wanted.
  *  seed      seed of the stochastic rounding.
  *  t         MBQ only: batch index in beta = min(0.9, (1+t)/(10+t))  (eq. (alpha update)).
  */
@@ -80,7 +94,7 @@ typedef struct {
   int64_t  m;
   int64_t  channels;
   int32_t  rounding;
-  int32_t  reserved;
+  int32_t  layout;
   uint64_t seed;
   int64_t  t;
 } accept_desc;
@@ -90,6 +104,7 @@ typedef struct {
  *   UNIFORM: header = 4*max(channels,1) bytes (float32 scale s per range group),
  *            payload = ceil(N*k/8) bytes.
  *   MBQ:     header = 4*(k+1) bytes (alpha_t[0..k), then m_q), payload = ceil(n/8)*m*k bytes.
+ *   Payload of the comparison layouts: see accept_desc.layout.
  * On a wire the two are concatenated header first; the total equals the paper's formulas.
  * Host-only; needs no GPU.
  */

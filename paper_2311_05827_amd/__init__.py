@@ -12,6 +12,7 @@ _BINDING_NAMES = (
     "accept_decompress", "accept_mbq_init", "accept_compress_timed", "accept_decompress_timed",
     "accept_bits_schedule", "accept_stage_name", "alloc_outputs", "dtype_code", "status_string", "version",
     "UNIFORM", "MBQ", "F32", "BF16", "ROUND_NEAREST_EVEN", "ROUND_STOCHASTIC",
+    "LAYOUT_PACKED", "LAYOUT_BATCH", "LAYOUT_UNENCODED",
 )
 
 

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libaccept.so")
 UNIFORM, MBQ = 0, 1
 F32, BF16 = 0, 1
 ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
+LAYOUT_PACKED, LAYOUT_BATCH, LAYOUT_UNENCODED = 0, 1, 2
 MAX_STAGES = 8
 
 STATUS_NAMES = {0: "ACCEPT_OK", 1: "ACCEPT_ERR_INVALID_ARG", 2: "ACCEPT_ERR_UNSUPPORTED",
@@ -35,7 +36,7 @@ class Desc(ctypes.Structure):
         ("scheme", ctypes.c_int32), ("bits", ctypes.c_int32),
         ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
         ("n", ctypes.c_int64), ("m", ctypes.c_int64), ("channels", ctypes.c_int64),
-        ("rounding", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("rounding", ctypes.c_int32), ("layout", ctypes.c_int32),
         ("seed", ctypes.c_uint64), ("t", ctypes.c_int64),
     ]
 
@@ -85,9 +86,10 @@ def _check(st, where):
         raise AcceptError(st, where)
 
 
-def make_desc(scheme, bits, n, m, channels=0, in_dtype=F32, out_dtype=F32, rounding=0, seed=0, t=0):
+def make_desc(scheme, bits, n, m, channels=0, in_dtype=F32, out_dtype=F32, rounding=0, seed=0, t=0,
+              layout=LAYOUT_PACKED):
     return Desc(int(scheme), int(bits), int(in_dtype), int(out_dtype), int(n), int(m), int(channels),
-                int(rounding), 0, int(seed), int(t))
+                int(rounding), int(layout), int(seed), int(t))
 
 
 def accept_packed_size(desc):

@@ -21,14 +21,18 @@ accept_status check_desc(const accept_desc* d) {
   if (d->in_dtype != ACCEPT_F32 && d->in_dtype != ACCEPT_BF16) return ACCEPT_ERR_INVALID_ARG;
   if (d->out_dtype != ACCEPT_F32 && d->out_dtype != ACCEPT_BF16) return ACCEPT_ERR_INVALID_ARG;
   if (d->channels < 0 || d->channels > kMaxChannels) return ACCEPT_ERR_INVALID_ARG;
+  if (d->layout != ACCEPT_LAYOUT_PACKED && d->layout != ACCEPT_LAYOUT_BATCH && d->layout != ACCEPT_LAYOUT_UNENCODED)
+    return ACCEPT_ERR_INVALID_ARG;
   if (d->scheme == ACCEPT_UNIFORM) {
     if (d->bits < 2 || d->bits > 8) return ACCEPT_ERR_INVALID_ARG;
+    if (d->layout == ACCEPT_LAYOUT_BATCH && 8 % d->bits != 0) return ACCEPT_ERR_INVALID_ARG;
     if (d->channels > 1 && d->m % d->channels != 0) return ACCEPT_ERR_INVALID_ARG;
     if (d->rounding != ACCEPT_ROUND_NEAREST_EVEN && d->rounding != ACCEPT_ROUND_STOCHASTIC)
       return ACCEPT_ERR_INVALID_ARG;
   } else {
     if (d->bits < 1 || d->bits > 8) return ACCEPT_ERR_INVALID_ARG;
     if (d->channels > 1) return ACCEPT_ERR_INVALID_ARG;
+    if (d->layout == ACCEPT_LAYOUT_BATCH) return ACCEPT_ERR_INVALID_ARG;
     if (d->rounding != ACCEPT_ROUND_NEAREST_EVEN) return ACCEPT_ERR_INVALID_ARG;
     if (d->t < 0) return ACCEPT_ERR_INVALID_ARG;
   }
@@ -100,11 +104,19 @@ accept_status accept_packed_size(const accept_desc* desc, size_t* header_bytes, 
   const int64_t k = desc->bits;
   if (desc->scheme == ACCEPT_MBQ) {
     *header_bytes = size_t(4 * (k + 1));
-    *payload_bytes = size_t(((desc->n + 7) / 8) * desc->m * k);
+    *payload_bytes = desc->layout == ACCEPT_LAYOUT_UNENCODED ? size_t(desc->n * desc->m * k)
+                                                             : size_t(((desc->n + 7) / 8) * desc->m * k);
   } else {
     const int64_t C = desc->channels > 1 ? desc->channels : 1;
     *header_bytes = size_t(4 * C);
-    *payload_bytes = size_t((desc->n * desc->m * k + 7) / 8);
+    if (desc->layout == ACCEPT_LAYOUT_UNENCODED) {
+      *payload_bytes = size_t(desc->n * desc->m);
+    } else if (desc->layout == ACCEPT_LAYOUT_BATCH) {
+      const int64_t per = 8 / k;
+      *payload_bytes = size_t(((desc->n + per - 1) / per) * desc->m);
+    } else {
+      *payload_bytes = size_t((desc->n * desc->m * k + 7) / 8);
+    }
   }
   return ACCEPT_OK;
 }
@@ -167,13 +179,20 @@ accept_status accept_decompress_timed(const accept_desc* desc, const void* heade
 
 const char* accept_stage_name(const accept_desc* desc, int is_decompress, int i) {
   if (check_desc(desc) != ACCEPT_OK || i < 0) return nullptr;
+  const bool plain = desc->layout != ACCEPT_LAYOUT_PACKED;
   if (is_decompress) {
     if (i != 0) return nullptr;
+    if (plain) return desc->scheme == ACCEPT_UNIFORM ? "dequant_plain" : "mbq_decode_plain";
     return desc->scheme == ACCEPT_UNIFORM ? "unpack_dequant" : "mbq_decode";
   }
   if (desc->scheme == ACCEPT_MBQ) {
     static const char* const names[] = {"mbq_encode", "mbq_finalize"};
-    return i < 2 ? names[i] : nullptr;
+    static const char* const names_plain[] = {"mbq_encode_plain", "mbq_finalize"};
+    return i < 2 ? (plain ? names_plain[i] : names[i]) : nullptr;
+  }
+  if (plain) {
+    static const char* const names[] = {"range", "range_finalize", "quantize_plain"};
+    return i < 3 ? names[i] : nullptr;
   }
   if (desc->channels > 1) {
     static const char* const names[] = {"range", "range_finalize", "quantize_pack"};

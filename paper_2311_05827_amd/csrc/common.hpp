@@ -195,6 +195,29 @@ __device__ __forceinline__ void store_vec(bf16_t* p, const float (&f)[8]) {
 __device__ __forceinline__ void store_one(float* p, float f) { *p = f; }
 __device__ __forceinline__ void store_one(bf16_t* p, float f) { p->bits = uint16_t(bf16_rne(f)); }
 
+// Four consecutive elements (16 bytes of float32, 8 bytes of bfloat16; p aligned to that).
+template <typename T>
+__device__ __forceinline__ void load_quad(const T* p, float (&f)[4]) {
+  if constexpr (sizeof(T) == 4) {
+    widen(load16_stream(p), f);
+  } else {
+    const uint2 v = *reinterpret_cast<const uint2*>(p);
+    f[0] = u32_as_f32(v.x << 16); f[1] = u32_as_f32(v.x & 0xFFFF0000u);
+    f[2] = u32_as_f32(v.y << 16); f[3] = u32_as_f32(v.y & 0xFFFF0000u);
+  }
+}
+template <typename T>
+__device__ __forceinline__ void store_quad(T* p, const float (&f)[4]) {
+  if constexpr (sizeof(T) == 4) {
+    store_vec(p, f);
+  } else {
+    uint2 v;
+    v.x = bf16_rne(f[0]) | (bf16_rne(f[1]) << 16);
+    v.y = bf16_rne(f[2]) | (bf16_rne(f[3]) << 16);
+    *reinterpret_cast<uint2*>(p) = v;
+  }
+}
+
 // Lane exchange inside a row of 16 lanes with a DPP control word (all lanes stay valid).
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {

@@ -698,6 +698,151 @@ __global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* _
   header[K] = float((dot - Sx) / n_elems);
 }
 
+// ================================================ comparison layout: one byte per binary base
+// ACCEPT_LAYOUT_UNENCODED: B itself, +1 / -1 as bytes, element-major with the k bases
+// innermost ("w/o enc." in the paper's size table).  Same levels, same sums and the same
+// finalize kernel as the bit-plane path; plain flat loops, four elements per thread and step.
+template <typename T, int K>
+__global__ __launch_bounds__(kBlock) void mbq_encode_plain_kernel(const T* __restrict__ x,
+                                                                  const float* __restrict__ alpha_prev,
+                                                                  uint8_t* __restrict__ payload,
+                                                                  double* __restrict__ partials, int64_t N) {
+  constexpr int NW = (K + 3) / 4;
+  constexpr int NPAIR = K * (K - 1) / 2;
+  constexpr int NSTAT = nstat_of(K);
+  __shared__ EncodeTables<K> tb;
+  __shared__ StatScratch red;
+  const int tid = threadIdx.x;
+  build_encode_tables<K>(alpha_prev, tb);
+  const int maxcnt = __builtin_amdgcn_readfirstlane(tb.maxcnt);
+  EncodeStats<K> st;
+  st.Sx = 0.0;
+#pragma unroll
+  for (int p = 0; p < K; ++p) { st.H[p] = 0.0; st.cnt[p] = 0; }
+#pragma unroll
+  for (int i = 0; i < (NPAIR > 0 ? NPAIR : 1); ++i) st.dis[i] = 0;
+
+  // one element: level, sums, and its k bytes (+1 -> 0x01, -1 -> 0xFF) into bytes[0..K)
+  auto element = [&](float v, uint8_t (&bytes)[K], float (&h32)[K], float& sx32) {
+    uint32_t sp[NW];
+    encode_elem<K>(tb, v, maxcnt, sp, h32, sx32);
+    uint32_t bit[K];
+#pragma unroll
+    for (int p = 0; p < K; ++p) {
+      bit[p] = (sp[p / 4] >> (8 * (p % 4))) & 1u;
+      bytes[p] = bit[p] ? uint8_t(0x01) : uint8_t(0xFF);
+      st.cnt[p] += bit[p];
+    }
+    int pi = 0;
+#pragma unroll
+    for (int p = 0; p < K; ++p)
+#pragma unroll
+      for (int q = p + 1; q < K; ++q) st.dis[pi++] += bit[p] ^ bit[q];
+  };
+
+  const int64_t quads = N / 4;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  const int64_t gtid = int64_t(blockIdx.x) * kBlock + tid;
+  for (int64_t u = gtid; u < quads; u += stride) {
+    float f[4];
+    load_quad<T>(x + 4 * u, f);
+    float h32[K];
+    float sx32 = 0.0f;
+#pragma unroll
+    for (int p = 0; p < K; ++p) h32[p] = 0.0f;
+    uint32_t out[K];  // 4 elements x K bytes = K dwords
+#pragma unroll
+    for (int w = 0; w < K; ++w) out[w] = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      uint8_t bytes[K];
+      element(f[e], bytes, h32, sx32);
+#pragma unroll
+      for (int p = 0; p < K; ++p) {
+        const int b = e * K + p;
+        out[b / 4] |= uint32_t(bytes[p]) << (8 * (b % 4));
+      }
+    }
+    store_dwords<K>(reinterpret_cast<uint32_t*>(payload) + u * K, out);
+    st.Sx += double(sx32);
+#pragma unroll
+    for (int p = 0; p < K; ++p) st.H[p] += double(h32[p]);
+  }
+  {
+    const int64_t i = quads * 4 + gtid;
+    if (i < N) {
+      float h32[K];
+      float sx32 = 0.0f;
+#pragma unroll
+      for (int p = 0; p < K; ++p) h32[p] = 0.0f;
+      uint8_t bytes[K];
+      element(load_one(x + i), bytes, h32, sx32);
+#pragma unroll
+      for (int p = 0; p < K; ++p) payload[i * K + p] = bytes[p];
+      st.Sx += double(sx32);
+#pragma unroll
+      for (int p = 0; p < K; ++p) st.H[p] += double(h32[p]);
+    }
+  }
+  double sv[NSTAT];
+#pragma unroll
+  for (int p = 0; p < K; ++p) sv[p] = st.H[p];
+  sv[K] = st.Sx;
+#pragma unroll
+  for (int p = 0; p < K; ++p) sv[K + 1 + p] = double(st.cnt[p]);
+#pragma unroll
+  for (int i = 0; i < NPAIR; ++i) sv[2 * K + 1 + i] = double(st.dis[i]);
+  const double total = block_sum_stats<NSTAT>(sv, red);
+  if (tid < NSTAT) partials[int64_t(tid) * gridDim.x + blockIdx.x] = total;
+}
+
+template <typename TO, int K>
+__global__ __launch_bounds__(kBlock) void mbq_decode_plain_kernel(const uint8_t* __restrict__ payload,
+                                                                  const float* __restrict__ header,
+                                                                  TO* __restrict__ xhat, int64_t N) {
+  constexpr int P = 1 << K;
+  __shared__ float lut[P];
+  const int tid = threadIdx.x;
+  if (tid < P) {
+    float v = 0.0f;
+#pragma unroll
+    for (int p = 0; p < K; ++p) {
+      const float a = header[p];
+      v = __fadd_rn(v, ((tid >> p) & 1) ? a : -a);
+    }
+    lut[tid] = __fsub_rn(v, header[K]);
+  }
+  __syncthreads();
+  const int64_t quads = N / 4;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  const int64_t gtid = int64_t(blockIdx.x) * kBlock + tid;
+  for (int64_t u = gtid; u < quads; u += stride) {
+    uint32_t w[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) w[i] = reinterpret_cast<const uint32_t*>(payload)[u * K + i];
+    float f[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      uint32_t pat = 0;
+#pragma unroll
+      for (int p = 0; p < K; ++p) {
+        const int b = e * K + p;
+        const uint32_t byte = (w[b / 4] >> (8 * (b % 4))) & 0xFFu;
+        pat |= (((byte >> 7) & 1u) ^ 1u) << p;  // +1 (0x01) -> bit 1, -1 (0xFF) -> bit 0
+      }
+      f[e] = lut[pat];
+    }
+    store_quad<TO>(xhat + 4 * u, f);
+  }
+  const int64_t i = quads * 4 + gtid;
+  if (i < N) {
+    uint32_t pat = 0;
+#pragma unroll
+    for (int p = 0; p < K; ++p) pat |= (((uint32_t(payload[i * K + p]) >> 7) & 1u) ^ 1u) << p;
+    store_one(xhat + i, lut[pat]);
+  }
+}
+
 // ====================================================================== decode (D1 + D2)
 template <typename TO, int K, int VEC>
 __global__ __launch_bounds__(kBlock) void mbq_decode_kernel(const uint8_t* __restrict__ payload,
@@ -889,13 +1034,54 @@ MPlan make_mplan(const accept_desc& d) {
   return p;
 }
 
+template <typename T>
+hipError_t encode_plain_k(const accept_desc& d, int grid, const T* x, const float* alpha_prev, uint8_t* payload,
+                          double* partials, hipStream_t s) {
+  const int64_t N = d.n * d.m;
+#define ACCEPT_ENC(KK)                                                                                          \
+  case KK:                                                                                                      \
+    hipLaunchKernelGGL((mbq_encode_plain_kernel<T, KK>), dim3(grid), dim3(kBlock), 0, s, x, alpha_prev, payload, \
+                       partials, N);                                                                            \
+    break;
+  switch (d.bits) {
+    ACCEPT_ENC(1) ACCEPT_ENC(2) ACCEPT_ENC(3) ACCEPT_ENC(4) ACCEPT_ENC(5) ACCEPT_ENC(6) ACCEPT_ENC(7) ACCEPT_ENC(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef ACCEPT_ENC
+  return hipGetLastError();
+}
+
+template <typename TO>
+hipError_t decode_plain_k(const accept_desc& d, const uint8_t* payload, const float* header, TO* xhat,
+                          hipStream_t s) {
+  const int64_t N = d.n * d.m;
+  const int grid = grid_for(N / 4 + 4, kDecodeGridMax);
+#define ACCEPT_DEC(KK)                                                                                       \
+  case KK:                                                                                                   \
+    hipLaunchKernelGGL((mbq_decode_plain_kernel<TO, KK>), dim3(grid), dim3(kBlock), 0, s, payload, header, \
+                       xhat, N);                                                                             \
+    break;
+  switch (d.bits) {
+    ACCEPT_DEC(1) ACCEPT_DEC(2) ACCEPT_DEC(3) ACCEPT_DEC(4) ACCEPT_DEC(5) ACCEPT_DEC(6) ACCEPT_DEC(7) ACCEPT_DEC(8)
+    default: return hipErrorInvalidValue;
+  }
+#undef ACCEPT_DEC
+  return hipGetLastError();
+}
+
 hipError_t launch_mbq_compress(const accept_desc& d, const MPlan& p, const void* x, const float* alpha_prev,
                                void* header, void* payload, void* ws, hipStream_t s, StageTimer* tm) {
   double* partials = static_cast<double*>(ws);
   uint8_t* pl = static_cast<uint8_t*>(payload);
   hipError_t e;
   mark(tm, s);
-  if (d.in_dtype == ACCEPT_BF16) {
+  int nrec = p.grid;
+  if (d.layout == ACCEPT_LAYOUT_UNENCODED) {
+    nrec = grid_for(d.n * d.m / 4 + 4, kEncodeGridMax);
+    e = d.in_dtype == ACCEPT_BF16
+            ? encode_plain_k<bf16_t>(d, nrec, static_cast<const bf16_t*>(x), alpha_prev, pl, partials, s)
+            : encode_plain_k<float>(d, nrec, static_cast<const float*>(x), alpha_prev, pl, partials, s);
+  } else if (d.in_dtype == ACCEPT_BF16) {
     const bf16_t* xb = static_cast<const bf16_t*>(x);
     e = p.vec == 8 ? encode_k<bf16_t, 8>(d, p, xb, alpha_prev, pl, partials, s)
                    : encode_k<bf16_t, 1>(d, p, xb, alpha_prev, pl, partials, s);
@@ -910,7 +1096,7 @@ hipError_t launch_mbq_compress(const accept_desc& d, const MPlan& p, const void*
   float* hdr = static_cast<float*>(header);
 #define ACCEPT_FIN(KK)                                                                                         \
   case KK:                                                                                                     \
-    hipLaunchKernelGGL(mbq_finalize_kernel<KK>, dim3(1), dim3(kFinBlock), 0, s, partials, p.grid, alpha_prev, \
+    hipLaunchKernelGGL(mbq_finalize_kernel<KK>, dim3(1), dim3(kFinBlock), 0, s, partials, nrec, alpha_prev,   \
                        n_elems, double(d.t), hdr);                                                             \
     break;
   switch (d.bits) {
@@ -931,7 +1117,10 @@ hipError_t launch_mbq_decompress(const accept_desc& d, const void* header, const
   const int vec = vec_for(d.out_dtype, d.m);
   hipError_t e;
   mark(tm, s);
-  if (d.out_dtype == ACCEPT_BF16) {
+  if (d.layout == ACCEPT_LAYOUT_UNENCODED) {
+    e = d.out_dtype == ACCEPT_BF16 ? decode_plain_k<bf16_t>(d, pl, hd, static_cast<bf16_t*>(xhat), s)
+                                   : decode_plain_k<float>(d, pl, hd, static_cast<float*>(xhat), s);
+  } else if (d.out_dtype == ACCEPT_BF16) {
     bf16_t* o = static_cast<bf16_t*>(xhat);
     e = vec == 8 ? decode_k<bf16_t, 8>(d, pl, hd, o, s) : decode_k<bf16_t, 1>(d, pl, hd, o, s);
   } else {

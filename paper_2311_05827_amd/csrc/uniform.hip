@@ -469,6 +469,183 @@ hipError_t launch_quant(const accept_desc& d, const UPlan& p, const T* x, float*
   return hipGetLastError();
 }
 
+// ===================================================== comparison layouts (plain kernels)
+// ACCEPT_LAYOUT_BATCH and ACCEPT_LAYOUT_UNENCODED: the same quantizer, other ways of laying
+// the integers into bytes.  The bit width is a run-time argument here; the reciprocal of every
+// range group comes from the table that range_finalize_kernel writes.
+
+// k-bit code of one element, as quantize1 computes it (same arithmetic, run-time k).
+__device__ __forceinline__ uint32_t quantize_any(float f, float r, int k, bool stoch, uint64_t seed, int64_t idx) {
+  const int half = 1 << (k - 1);
+  const uint32_t mask = (1u << k) - 1u;
+  const float v = __fmul_rn(f, r);
+  if (!stoch) {
+    const float t = __fadd_rn(v, kRoundMagic + float(k == 8 ? 0 : half));
+    return f32_as_u32(t) & mask;
+  }
+  const float fl = floorf(v);
+  const float pr = __fsub_rn(v, fl);
+  const float u = counter_uniform(seed, uint64_t(idx));
+  int q = int(fl) + (u < pr ? 1 : 0);
+  q = min(max(q, -half), half - 1);
+  return (k == 8) ? (uint32_t(q) & 0xFFu) : uint32_t(q + half);
+}
+// Signed value of a code.
+__device__ __forceinline__ int code_to_q(uint32_t code, int k) {
+  return k == 8 ? int(int8_t(code)) : int(code) - (1 << (k - 1));
+}
+
+// UNENCODED: byte i = q_i (two's complement).  Four elements per thread and step, the last
+// N % 4 elements one per thread.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void quantize_bytes_kernel(const T* __restrict__ x,
+                                                                const float* __restrict__ rtab,
+                                                                uint8_t* __restrict__ payload, int64_t N, int64_t m,
+                                                                int64_t seg_len, int k, int stoch, uint64_t seed) {
+  const int64_t quads = N / 4;
+  const bool one = seg_len == m;  // a single range group
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  const int64_t gtid = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  for (int64_t u = gtid; u < quads; u += stride) {
+    float f[4];
+    load_quad<T>(x + 4 * u, f);
+    uint32_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int64_t i = 4 * u + e;
+      const float r = one ? rtab[0] : rtab[(i % m) / seg_len];
+      w |= (uint32_t(code_to_q(quantize_any(f[e], r, k, stoch != 0, seed, i), k)) & 0xFFu) << (8 * e);
+    }
+    *reinterpret_cast<uint32_t*>(payload + 4 * u) = w;
+  }
+  const int64_t i = quads * 4 + gtid;
+  if (i < N) {
+    const float r = one ? rtab[0] : rtab[(i % m) / seg_len];
+    payload[i] = uint8_t(code_to_q(quantize_any(load_one(x + i), r, k, stoch != 0, seed, i), k));
+  }
+}
+
+template <typename TO>
+__global__ __launch_bounds__(kBlock) void dequant_bytes_kernel(const uint8_t* __restrict__ payload,
+                                                               const float* __restrict__ header,
+                                                               TO* __restrict__ xhat, int64_t N, int64_t m,
+                                                               int64_t seg_len) {
+  const int64_t quads = N / 4;
+  const bool one = seg_len == m;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  const int64_t gtid = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  for (int64_t u = gtid; u < quads; u += stride) {
+    const uint32_t w = *reinterpret_cast<const uint32_t*>(payload + 4 * u);
+    float f[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int64_t i = 4 * u + e;
+      const float s = one ? header[0] : header[(i % m) / seg_len];
+      f[e] = __fmul_rn(float(int(int8_t(w >> (8 * e)))), s);
+    }
+    store_quad<TO>(xhat + 4 * u, f);
+  }
+  const int64_t i = quads * 4 + gtid;
+  if (i < N) {
+    const float s = one ? header[0] : header[(i % m) / seg_len];
+    store_one(xhat + i, __fmul_rn(float(int(int8_t(payload[i]))), s));
+  }
+}
+
+// BATCH: byte g*m + j = codes of rows g*per .. g*per+per-1 of column j (per = 8/k), first row
+// in the most significant bits.  With m % 4 == 0 a thread takes four columns (16-byte row
+// loads, one dword store); otherwise one byte per thread.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void quantize_batch_kernel(const T* __restrict__ x,
+                                                                const float* __restrict__ rtab,
+                                                                uint8_t* __restrict__ payload, int64_t n, int64_t m,
+                                                                int64_t seg_len, int k, int stoch, uint64_t seed) {
+  const int per = 8 / k;
+  const int64_t G = (n + per - 1) / per;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  const int64_t gtid = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  if (m % 4 == 0) {
+    const int64_t m4 = m / 4;
+    for (int64_t u = gtid; u < G * m4; u += stride) {
+      const int64_t g = u / m4, j0 = (u - g * m4) * 4;
+      float r[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[e] = rtab[(j0 + e) / seg_len];
+      uint32_t w = 0;
+      for (int i = 0; i < per; ++i) {
+        const int64_t row = g * per + i;
+        if (row >= n) break;
+        float f[4];
+        load_quad<T>(x + row * m + j0, f);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          w |= quantize_any(f[e], r[e], k, stoch != 0, seed, row * m + j0 + e) << (8 * e + k * (per - 1 - i));
+      }
+      *reinterpret_cast<uint32_t*>(payload + g * m + j0) = w;
+    }
+  } else {
+    for (int64_t u = gtid; u < G * m; u += stride) {
+      const int64_t g = u / m, j = u - g * m;
+      const float r = rtab[j / seg_len];
+      uint32_t b = 0;
+      for (int i = 0; i < per; ++i) {
+        const int64_t row = g * per + i;
+        if (row >= n) break;
+        b |= quantize_any(load_one(x + row * m + j), r, k, stoch != 0, seed, row * m + j) << (k * (per - 1 - i));
+      }
+      payload[u] = uint8_t(b);
+    }
+  }
+}
+
+template <typename TO>
+__global__ __launch_bounds__(kBlock) void dequant_batch_kernel(const uint8_t* __restrict__ payload,
+                                                               const float* __restrict__ header,
+                                                               TO* __restrict__ xhat, int64_t n, int64_t m,
+                                                               int64_t seg_len, int k) {
+  const int per = 8 / k;
+  const uint32_t mask = (1u << k) - 1u;
+  const int64_t G = (n + per - 1) / per;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  const int64_t gtid = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  if (m % 4 == 0) {
+    const int64_t m4 = m / 4;
+    for (int64_t u = gtid; u < G * m4; u += stride) {
+      const int64_t g = u / m4, j0 = (u - g * m4) * 4;
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(payload + g * m + j0);
+      float s[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] = header[(j0 + e) / seg_len];
+      for (int i = 0; i < per; ++i) {
+        const int64_t row = g * per + i;
+        if (row >= n) break;
+        float f[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          f[e] = __fmul_rn(float(code_to_q((w >> (8 * e + k * (per - 1 - i))) & mask, k)), s[e]);
+        store_quad<TO>(xhat + row * m + j0, f);
+      }
+    }
+  } else {
+    for (int64_t u = gtid; u < G * m; u += stride) {
+      const int64_t g = u / m, j = u - g * m;
+      const uint32_t b = payload[u];
+      const float s = header[j / seg_len];
+      for (int i = 0; i < per; ++i) {
+        const int64_t row = g * per + i;
+        if (row >= n) break;
+        store_one(xhat + row * m + j, __fmul_rn(float(code_to_q((b >> (k * (per - 1 - i))) & mask, k)), s));
+      }
+    }
+  }
+}
+
+int plain_grid(int64_t units) {
+  int64_t blocks = (units + kBlock - 1) / kBlock;
+  if (blocks < 1) blocks = 1;
+  return int(blocks < 8192 ? blocks : 8192);
+}
+
 template <typename T, int K>
 hipError_t launch_quant_k(const accept_desc& d, const UPlan& p, const T* x, float* header, uint32_t* payload,
                           const float* partials, const float* rtab, hipStream_t s) {
@@ -506,15 +683,34 @@ hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, floa
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   mark(tm, s);
-  if (p.mode != U_TENSOR) {
-    // U_GENERIC stores one maximum per channel: finalize reads it as a 1 x C x 1 table.
+  const bool plain = d.layout != ACCEPT_LAYOUT_PACKED;
+  if (p.mode != U_TENSOR || plain) {
+    // U_GENERIC stores one maximum per channel: finalize reads it as a 1 x C x 1 table; the
+    // per-tensor pass leaves range_grid maxima: one row, one channel, range_grid chunks.
     const int64_t rows = p.mode == U_SEGMENTED ? d.n : 1;
-    const int64_t cps = p.mode == U_SEGMENTED ? p.cps : 1;
+    const int64_t cps = p.mode == U_SEGMENTED ? p.cps : (p.mode == U_TENSOR ? p.range_grid : 1);
     hipLaunchKernelGGL(range_finalize_kernel, dim3(unsigned(p.C)), dim3(kWave), 0, s, partials, rows, p.C, cps,
                        d.bits, header, rtab);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     mark(tm, s);
+  }
+  if (plain) {
+    uint8_t* pl = reinterpret_cast<uint8_t*>(payload);
+    const int stoch = d.rounding == ACCEPT_ROUND_STOCHASTIC ? 1 : 0;
+    if (d.layout == ACCEPT_LAYOUT_UNENCODED) {
+      hipLaunchKernelGGL((quantize_bytes_kernel<T>), dim3(plain_grid(p.N / 4 + 4)), dim3(kBlock), 0, s, x, rtab, pl,
+                         p.N, p.m, p.seg_len, d.bits, stoch, d.seed);
+    } else {
+      const int per = 8 / d.bits;
+      const int64_t G = (d.n + per - 1) / per;
+      hipLaunchKernelGGL((quantize_batch_kernel<T>), dim3(plain_grid(p.m % 4 == 0 ? G * (p.m / 4) : G * p.m)),
+                         dim3(kBlock), 0, s, x, rtab, pl, d.n, p.m, p.seg_len, d.bits, stoch, d.seed);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    mark(tm, s);
+    return hipSuccess;
   }
   switch (d.bits) {
     case 2: e = launch_quant_k<T, 2>(d, p, x, header, payload, partials, rtab, s); break;
@@ -566,6 +762,21 @@ hipError_t launch_dequant(const accept_desc& d, const float* header, const uint3
 template <typename TO>
 hipError_t decompress_typed(const accept_desc& d, const float* header, const uint32_t* payload, TO* xhat,
                             hipStream_t s) {
+  if (d.layout != ACCEPT_LAYOUT_PACKED) {
+    const uint8_t* pl = reinterpret_cast<const uint8_t*>(payload);
+    const int64_t N = d.n * d.m;
+    const int64_t seg_len = d.m / (d.channels > 1 ? d.channels : 1);
+    if (d.layout == ACCEPT_LAYOUT_UNENCODED) {
+      hipLaunchKernelGGL((dequant_bytes_kernel<TO>), dim3(plain_grid(N / 4 + 4)), dim3(kBlock), 0, s, pl, header,
+                         xhat, N, d.m, seg_len);
+    } else {
+      const int per = 8 / d.bits;
+      const int64_t G = (d.n + per - 1) / per;
+      hipLaunchKernelGGL((dequant_batch_kernel<TO>), dim3(plain_grid(d.m % 4 == 0 ? G * (d.m / 4) : G * d.m)),
+                         dim3(kBlock), 0, s, pl, header, xhat, d.n, d.m, seg_len, d.bits);
+    }
+    return hipGetLastError();
+  }
   const bool perch = d.channels > 1;
 #define ACCEPT_DQ(KK)                                                              \
   case KK:                                                                         \

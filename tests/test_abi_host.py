@@ -46,7 +46,8 @@ def test_library_exports_every_declared_symbol(A):
 def test_desc_layout_matches_header(A):
     assert ctypes.sizeof(A.Desc) == 64
     assert A.Desc.n.offset == 16 and A.Desc.m.offset == 24 and A.Desc.channels.offset == 32
-    assert A.Desc.rounding.offset == 40 and A.Desc.seed.offset == 48 and A.Desc.t.offset == 56
+    assert A.Desc.rounding.offset == 40 and A.Desc.layout.offset == 44
+    assert A.Desc.seed.offset == 48 and A.Desc.t.offset == 56
 
 
 @pytest.mark.parametrize("scheme", [0, 1])
@@ -60,6 +61,11 @@ def test_packed_size_matches_oracle(A, scheme):
             assert A.accept_packed_size(d) == orc.packed_size(scheme, bits, n, m, ch)
             ws = A.accept_workspace_size(d)
             assert ws > 0 and ws % 256 == 0 and ws < (1 << 26)
+            layouts = [A.LAYOUT_UNENCODED] + ([A.LAYOUT_BATCH] if scheme == 0 and 8 % bits == 0 else [])
+            for layout in layouts:
+                dl = A.make_desc(scheme, bits, n, m, channels=ch, layout=layout)
+                assert A.accept_packed_size(dl) == orc.packed_size(scheme, bits, n, m, ch, layout)
+                assert A.accept_workspace_size(dl) == ws
 
 
 def test_bits_schedule_matches_oracle_and_paper(A):
@@ -94,6 +100,9 @@ def test_invalid_arguments_are_rejected_before_any_launch(A):
         A.make_desc(0, 4, 4, 4, rounding=5),
         A.make_desc(1, 3, 4, 4, rounding=1),
         A.make_desc(1, 3, 4, 4, t=-1),
+        A.make_desc(0, 4, 4, 4, layout=3),
+        A.make_desc(0, 3, 4, 4, layout=A.LAYOUT_BATCH),   # 8/k rows share a byte: k must divide 8
+        A.make_desc(1, 3, 4, 4, layout=A.LAYOUT_BATCH),   # the batch layout is the backward encoder's
     ]
     h, p = ctypes.c_size_t(0), ctypes.c_size_t(0)
     for d in bad:
@@ -115,3 +124,6 @@ def test_invalid_arguments_are_rejected_before_any_launch(A):
     assert lib.accept_mbq_init(ctypes.byref(good), V(0x1000), V(0x2000), V(0x4000), None) == INVALID
     assert A.accept_stage_name(good, 0, 0) == "range" and A.accept_stage_name(good, 0, 1) == "quantize_pack"
     assert A.accept_stage_name(good, 0, 2) is None and A.accept_stage_name(mbq, 1, 0) == "mbq_decode"
+    plain = A.make_desc(0, 4, 4, 4, layout=A.LAYOUT_BATCH)
+    assert [A.accept_stage_name(plain, 0, i) for i in range(4)] == ["range", "range_finalize", "quantize_plain", None]
+    assert A.accept_stage_name(plain, 1, 0) == "dequant_plain"
