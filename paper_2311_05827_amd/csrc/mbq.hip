@@ -1025,7 +1025,19 @@ MPlan make_mplan(const accept_desc& d) {
   p.vec = vec_for(d.in_dtype, d.m);
   p.G = (d.n + 7) / 8;
   p.items = p.G * (d.m / p.vec);
-  p.grid = grid_for(p.items, kEncodeGridMax);
+  // Grid of the encode kernel.  Its fast loop runs whole rounds (every thread of the grid has an
+  // item) and what is left over goes one column per thread, so a tensor with fewer items than
+  // the largest grid has threads gets the largest grid that still fills one round (rounding the
+  // grid up instead would leave every item to the slower leftover path).  The columns of a last,
+  // partial row group also go one per thread: the grid is at least wide enough for them.
+  {
+    const int64_t items_full = (d.n / 8) * (d.m / p.vec);
+    int64_t blocks = items_full / kBlock;
+    const int64_t tail_blocks = (d.n % 8 != 0) ? (d.m + kBlock - 1) / kBlock : 0;
+    if (blocks < tail_blocks) blocks = tail_blocks;
+    if (blocks < 1) blocks = 1;
+    p.grid = int(blocks < kEncodeGridMax ? blocks : kEncodeGridMax);
+  }
   p.nstat = nstat_of(d.bits);
   // records of the encode kernel (stat-major, kEncodeGridMax wide at most) and, for the
   // residue initialisation, kInitGrid partial sums: both fit the same area
