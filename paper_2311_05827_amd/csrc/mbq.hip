@@ -515,7 +515,7 @@ __global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel
                                                              const float* __restrict__ alpha_prev,
                                                              uint8_t* __restrict__ payload,
                                                              double* __restrict__ partials, int64_t n, int64_t m,
-                                                             int64_t ipg, int64_t items, ItemStep step) {
+                                                             int64_t ipg, ItemStep step) {
   constexpr int NPAIR = K * (K - 1) / 2;
   constexpr int NSTAT = nstat_of(K);
   __shared__ EncodeTables<K> tb;
@@ -973,7 +973,7 @@ hipError_t launch_encode(const accept_desc& d, const MPlan& p, const T* x, const
                          double* partials, hipStream_t s) {
   const int64_t ipg = d.m / VEC;
   hipLaunchKernelGGL((mbq_encode_kernel<T, K, VEC>), dim3(p.grid), dim3(kBlock), 0, s, x, alpha_prev, payload,
-                     partials, d.n, d.m, ipg, p.items, step_for(p.grid, ipg));
+                     partials, d.n, d.m, ipg, step_for(p.grid, ipg));
   return hipGetLastError();
 }
 
