@@ -104,7 +104,7 @@ struct EncodeTables {
   float lv_raw[P];
   float lv_sorted[P];
   uint32_t pat_sorted[P];
-  float tau[2 * P];                        // P-1 thresholds, then +inf padding
+  float tau[3 * P];                        // P-1 thresholds, then +inf padding (the windowed search reads past them)
   uint32_t spread[P * NW];                 // per sorted level: bit p of the sign pattern at bit 8*(p%4) of word p/4
   // k <= 4 only: row lo = {tau[lo] (or +inf), spread[lo]}, so that one 8-byte read at lo*8 and one
   // 4-byte read at lo*8 + 12 (= spread[lo+1]) give everything an element needs (two 8-byte reads
@@ -132,7 +132,7 @@ __device__ __forceinline__ void build_encode_tables(const float* __restrict__ al
   const int tid = threadIdx.x;
   if (tid == 0) tb.maxcnt = 1;
   build_levels<K>(alpha_prev, tb.lv_raw, tb.lv_sorted, tb.pat_sorted);
-  for (int i = tid; i < 2 * P; i += kBlock)
+  for (int i = tid; i < 3 * P; i += kBlock)
     tb.tau[i] = (i < P - 1) ? __fmul_rn(0.5f, __fadd_rn(tb.lv_sorted[i], tb.lv_sorted[i + 1])) : __builtin_inff();
   if (tid < P) {
     const uint32_t pat = tb.pat_sorted[tid];
@@ -274,9 +274,15 @@ __device__ __forceinline__ void encode_elem(const EncodeTables<K>& tb, float x, 
                                             uint32_t (&sp)[(K + 3) / 4], float (&a32)[K], float& sx32) {
   using TB = EncodeTables<K>;
   const int lo = tb.lut[f32_as_u32(x) >> (32 - kLutBits)] >> TB::LUT_SHIFT;
-  int idx = lo + ((x > tb.tau[lo]) ? 1 : 0);
+  // #{c < maxcnt : x > tau[lo + c]}: the thresholds are sorted, so the true compares form a
+  // prefix of tau[lo ..]; its length (at most maxcnt) is found by a branch-free binary search
+  // over a window of 2*top - 1 >= maxcnt entries, top = the largest power of two <= maxcnt.
+  // lo <= P-1 and the window is shorter than 2P: every read stays inside tau[3P).
+  int cnt = 0;
 #pragma nounroll
-  for (int c = 1; c < maxcnt; ++c) idx += (x > tb.tau[lo + c]) ? 1 : 0;
+  for (int step = 1 << (31 - __clz(maxcnt)); step >= 1; step >>= 1)
+    cnt += (x > tb.tau[lo + cnt + step - 1]) ? step : 0;
+  const int idx = lo + cnt;
 #pragma unroll
   for (int w = 0; w < TB::NW; ++w) sp[w] = tb.spread[idx * TB::NW + w];
   accumulate_elem<K>(x, sp, a32, sx32);
