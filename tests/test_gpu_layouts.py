@@ -7,7 +7,7 @@ import pytest
 
 import synthetic_inputs as si
 from oracle import accept_oracle as orc
-from tests.gpu_util import bytes_to_dev, dev_bytes, first_mismatch, out_to_numpy, to_dev, torch_mod
+from gpu_util import bytes_to_dev, dev_bytes, first_mismatch, out_to_numpy, to_dev, torch_mod
 
 pytestmark = pytest.mark.gpu
 
