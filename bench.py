@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of the benchmark tensor's size (205,520,896 B read + "
                          "as many written per copy): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--calls", default=None, metavar="CFG:S:K:C:DTYPE[,...]",
+                    help="only run compress + decompress of the named cells three times each, cold, e.g. "
+                         "cfg3_act:M:3:0:f32,cfg4_grad:U:8:256:f32 (for rocprofv3 counter runs per configuration)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (the codec has no multi-GPU path); use --gpus 1")
@@ -123,6 +126,33 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         log("copy calibration: 10 copies of %d bytes" % (N * 4))
+        return
+
+    if args.calls:
+        evict = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        for cell in args.calls.split(","):
+            name, scheme, k, C, dt = cell.split(":")
+            k, C, bf = int(k), int(C), dt == "bf16"
+            x_np = si.make(name)
+            cn, cm = si.as_nm(x_np)
+            x = torch.from_numpy(x_np.reshape(-1)).to(dev)
+            x = x.to(torch.bfloat16) if bf else x
+            tcode = A.BF16 if bf else A.F32
+            if scheme == "U":
+                d = A.make_desc(A.UNIFORM, k, cn, cm, channels=C, in_dtype=tcode, out_dtype=tcode)
+                alpha = None
+            else:
+                d = A.make_desc(A.MBQ, k, cn, cm, t=1, in_dtype=tcode, out_dtype=tcode)
+                alpha = A.accept_mbq_init(d, x)
+            h, p, w = A.alloc_outputs(d, dev)
+            out = torch.empty(cn * cm, dtype=x.dtype, device=dev)
+            for _ in range(3):
+                evict.sum()
+                A.accept_compress(d, x, alpha_prev=alpha, header=h, payload=p, workspace=w)
+                evict.sum()
+                A.accept_decompress(d, h, p, out=out)
+            torch.cuda.synchronize()
+            log("calls: %s done" % cell)
         return
 
     t0 = time.time()
