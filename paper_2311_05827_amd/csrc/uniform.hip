@@ -361,24 +361,17 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
 // Four consecutive codes starting at element index e0 (a multiple of 4): load the one or two
 // payload dwords that hold their 4k bits, view them as a big-endian 64-bit window, extract,
 // remove the offset by sign extension, multiply by s.
+// The payload words of four consecutive codes (hi: the dword holding the first bit; lo: the
+// next dword, needed only for widths whose 4-code fields can straddle two dwords).
+struct CodeWords {
+  uint32_t hi, lo;
+};
+// e0: element index of the first code (a multiple of 4), relative to a dword-aligned origin.
 template <int K>
-__device__ __forceinline__ void dequant4(const uint32_t* __restrict__ payload32, int64_t e0, float s, float* out) {
+__device__ __forceinline__ void convert_codes4(CodeWords c, int64_t e0, float s, float* out) {
   constexpr int W = 4 * K;
-  const int64_t bit = e0 * K;
-  const int64_t w0 = bit >> 5;
-  const int sh = int(bit & 31);
-  uint32_t hi, lo = 0;
-  if (32 % W != 0) {
-    // fields may straddle two dwords: always fetch the pair as one 8-byte load (the vector path
-    // stops one 32-element group before the end, so dword w0+1 always exists)
-    struct alignas(4) Pair { uint32_t a, b; };
-    const Pair pr = *reinterpret_cast<const Pair*>(payload32 + w0);
-    hi = __builtin_bswap32(pr.a);
-    lo = __builtin_bswap32(pr.b);
-  } else {
-    hi = __builtin_bswap32(payload32[w0]);
-  }
-  const uint64_t win = (uint64_t(hi) << 32) | lo;
+  const int sh = int((e0 * K) & 31);
+  const uint64_t win = (uint64_t(__builtin_bswap32(c.hi)) << 32) | __builtin_bswap32(c.lo);
   uint32_t piece = uint32_t(win >> (64 - W - sh));
   // Offset binary -> two's complement: flip the top bit of each k-bit field (k < 8).
   if (K < 8) {
@@ -390,6 +383,23 @@ __device__ __forceinline__ void dequant4(const uint32_t* __restrict__ payload32,
     const int q = __builtin_amdgcn_sbfe(int(piece), K * (3 - e), K);
     out[e] = __fmul_rn(float(q), s);
   }
+}
+template <int K>
+__device__ __forceinline__ void dequant4(const uint32_t* __restrict__ payload32, int64_t e0, float s, float* out) {
+  const int64_t w0 = (e0 * K) >> 5;
+  CodeWords c;
+  c.lo = 0;
+  if (32 % (4 * K) != 0) {
+    // fields may straddle two dwords: always fetch the pair as one 8-byte load (the vector path
+    // stops one 32-element group before the end, so dword w0+1 always exists)
+    struct alignas(4) Pair { uint32_t a, b; };
+    const Pair pr = *reinterpret_cast<const Pair*>(payload32 + w0);
+    c.hi = pr.a;
+    c.lo = pr.b;
+  } else {
+    c.hi = payload32[w0];
+  }
+  convert_codes4<K>(c, e0, s, out);
 }
 
 // Slow path: one element, byte loads guarded by the payload size.
@@ -429,6 +439,67 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(
   }
   const uint8_t* payload8 = reinterpret_cast<const uint8_t*>(payload32);
   for (int64_t i = fast_vecs * VEC + int64_t(blockIdx.x) * kBlock + threadIdx.x; i < N; i += stride) {
+    const float s = PERCH ? header[(i % m) / seg_len] : s_tensor;
+    store_one(xhat + i, dequant1<K>(payload8, i, payload_bytes, s));
+  }
+}
+
+// Tiled decoder: a workgroup takes the K KiB of payload of one 8192-element tile with 16-byte
+// loads that are contiguous across lanes, parks them in local memory, and every thread then
+// picks the dword (or dword pair) of each of its output vectors from there; output vector
+// j*256 + tid of the tile goes out as one 16-byte streaming store, contiguous across lanes.
+// (Reading the payload straight from global memory gives every lane a 4-byte load of which
+// half is used at k = 4: the small reads, not the stores, held the plain kernel back.)
+// Elements beyond the last whole tile take the scalar path.
+template <typename TO, int K, bool PERCH>
+__global__ __launch_bounds__(kBlock) void unpack_dequant_tiled_kernel(
+    const uint32_t* __restrict__ payload32, const float* __restrict__ header, TO* __restrict__ xhat, int64_t N,
+    int64_t full_tiles, int64_t payload_bytes, ChanGeom geom, int64_t m, int64_t seg_len) {
+  constexpr int VEC = Elem<TO>::VEC;
+  constexpr int VPT = kTileElems / VEC / kBlock;  // output vectors per thread and tile
+  constexpr int TILE_DW = K * (kTileElems / 32);  // payload dwords of a tile
+  constexpr int SWEEPS = (TILE_DW + 4 * kBlock - 1) / (4 * kBlock);
+  __shared__ __attribute__((aligned(16))) uint32_t tile[2][TILE_DW + 4];  // + one dword a straddling pair may touch
+  const int tid = threadIdx.x;
+  const float s_tensor = PERCH ? 0.0f : header[0];
+  ChanPos tile_pos{0, 0};
+  if (PERCH && full_tiles > 0) tile_pos = chan_init(geom, int64_t(blockIdx.x) * (kTileElems / VEC) + tid);
+  if (tid < 4) { tile[0][TILE_DW + tid] = 0u; tile[1][TILE_DW + tid] = 0u; }
+  int buf = 0;
+  for (int64_t t = blockIdx.x; t < full_tiles; t += gridDim.x, buf ^= 1) {
+    const uint32_t* src = payload32 + t * TILE_DW;  // 16-byte aligned: TILE_DW is a multiple of 4
+#pragma unroll
+    for (int w = 0; w < SWEEPS; ++w) {
+      const int dw = (w * kBlock + tid) * 4;
+      if (dw < TILE_DW) *reinterpret_cast<uint4*>(&tile[buf][dw]) = load16_stream(src + dw);
+    }
+    __syncthreads();  // double buffered: the next tile's writes go to the other half
+    ChanPos pos = tile_pos;
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+      float s = s_tensor;
+      if (PERCH) {
+        s = header[pos.ch];
+        chan_advance(geom, pos, geom.s256);
+      }
+      const int vec_in_tile = j * kBlock + tid;
+      float f[VEC];
+#pragma unroll
+      for (int h = 0; h < VEC / 4; ++h) {
+        const int e0 = vec_in_tile * VEC + 4 * h;  // element index inside the tile
+        const int bit = e0 * K;
+        CodeWords c;
+        c.hi = tile[buf][bit >> 5];
+        c.lo = (32 % (4 * K) != 0) ? tile[buf][(bit >> 5) + 1] : 0u;
+        convert_codes4<K>(c, e0, s, &f[4 * h]);
+      }
+      store_vec(xhat + (t * (kTileElems / VEC) + vec_in_tile) * VEC, f);
+    }
+    if (PERCH) chan_advance(geom, tile_pos, geom.sgrid);
+  }
+  const uint8_t* payload8 = reinterpret_cast<const uint8_t*>(payload32);
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  for (int64_t i = full_tiles * kTileElems + int64_t(blockIdx.x) * kBlock + tid; i < N; i += stride) {
     const float s = PERCH ? header[(i % m) / seg_len] : s_tensor;
     store_one(xhat + i, dequant1<K>(payload8, i, payload_bytes, s));
   }
@@ -754,6 +825,19 @@ hipError_t launch_dequant(const accept_desc& d, const float* header, const uint3
     g.s256 = g.sgrid;
   }
   const int64_t payload_bytes = (N * K + 7) / 8;
+  const int64_t full_tiles = fast ? N / kTileElems : 0;
+  if (full_tiles > 0) {
+    const int64_t tail = N - full_tiles * kTileElems;
+    int64_t want = full_tiles > (tail + kBlock - 1) / kBlock ? full_tiles : (tail + kBlock - 1) / kBlock;
+    const int tgrid = int(want < kDequantGridMax ? want : kDequantGridMax);
+    if (PERCH) {
+      g.s256 = make_step(kBlock, g.seg_vecs, C);
+      g.sgrid = make_step(int64_t(tgrid) * (kTileElems / VEC), g.seg_vecs, C);
+    }
+    hipLaunchKernelGGL((unpack_dequant_tiled_kernel<TO, K, PERCH>), dim3(tgrid), dim3(kBlock), 0, s, payload, header,
+                       xhat, N, full_tiles, payload_bytes, g, d.m, seg_len);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL((unpack_dequant_kernel<TO, K, PERCH>), dim3(grid), dim3(kBlock), 0, s, payload, header, xhat, N,
                      fast_vecs, payload_bytes, g, d.m, seg_len);
   return hipGetLastError();
