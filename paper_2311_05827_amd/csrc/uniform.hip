@@ -471,7 +471,9 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_tiled_kernel(
 #pragma unroll
     for (int w = 0; w < SWEEPS; ++w) {
       const int dw = (w * kBlock + tid) * 4;
-      if (dw < TILE_DW) *reinterpret_cast<uint4*>(&tile[buf][dw]) = load16_stream(src + dw);
+      // plain loads: a payload that was written a moment ago is often still in a cache, and
+      // streaming loads of such lines cost 9 us per call at the benchmark shape
+      if (dw < TILE_DW) *reinterpret_cast<uint4*>(&tile[buf][dw]) = load16(src + dw);
     }
     __syncthreads();  // double buffered: the next tile's writes go to the other half
     ChanPos pos = tile_pos;
