@@ -45,8 +45,10 @@ extern "C" {
 typedef enum {
   ACCEPT_OK = 0,
   ACCEPT_ERR_INVALID_ARG = 1,      /* null pointer, bad size, bits out of range, misaligned buffer */
-  ACCEPT_ERR_UNSUPPORTED = 2,      /* a combination this build does not implement            */
-  ACCEPT_ERR_BUFFER_TOO_SMALL = 3, /* reserved for callers that pass capacities               */
+  ACCEPT_ERR_UNSUPPORTED = 2,      /* valid, but beyond a fixed limit of the entry point called  */
+  ACCEPT_ERR_BUFFER_TOO_SMALL = 3, /* never returned by the C functions (they take no capacities);
+                                      the Python binding raises it for a tensor that is smaller
+                                      than accept_packed_size / accept_workspace_size require  */
   ACCEPT_ERR_HIP = 4               /* a HIP runtime call or kernel launch failed              */
 } accept_status;
 
@@ -146,6 +148,25 @@ accept_status accept_compress(const accept_desc* desc, const void* x_dev, const 
  */
 accept_status accept_decompress(const accept_desc* desc, const void* header_dev, const void* payload_dev,
                                 void* xhat_dev, void* hip_stream);
+
+/*
+ * accept_compress for callers that cannot allocate device memory or own no workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels, outputs and errors as accept_compress, except that the workspace is an
+ * array of ACCEPT_NOALLOC_SCRATCH_BYTES that is part of the library's device code: every GPU
+ * the library runs on holds its own copy from the first launch until the process ends.  The
+ * call allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine);
+ * its first use on a device looks the array's address up once (hipGetSymbolAddress).
+ * Descriptors whose accept_workspace_size exceeds ACCEPT_NOALLOC_SCRATCH_BYTES are rejected
+ * with ACCEPT_ERR_UNSUPPORTED before any HIP call (every MBQ descriptor and every per-tensor
+ * UNIFORM descriptor fits; per-channel ones fit up to about 250,000 (row, channel) segments).
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ * (different streams or threads) race; calls on one stream are safe.  Nothing in the array has
+ * to start at zero (the kernels write what they later read), so no clearing is enqueued.
+ */
+enum { ACCEPT_NOALLOC_SCRATCH_BYTES = 1 << 20 };
+accept_status accept_compress_noalloc(const accept_desc* desc, const void* x_dev, const float* alpha_prev_dev,
+                                      void* header_dev, void* payload_dev, void* hip_stream);
 
 /*
  * Residue-based initialisation of alpha at batch 0 of an epoch (paragraph "Forward

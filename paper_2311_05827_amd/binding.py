@@ -53,6 +53,7 @@ def _load():
     lib.accept_workspace_size.argtypes = [P(Desc), sz]
     lib.accept_compress.argtypes = [P(Desc), V, V, V, V, V, V]
     lib.accept_decompress.argtypes = [P(Desc), V, V, V, V]
+    lib.accept_compress_noalloc.argtypes = [P(Desc), V, V, V, V, V]
     lib.accept_mbq_init.argtypes = [P(Desc), V, V, V, V]
     lib.accept_compress_timed.argtypes = [P(Desc), V, V, V, V, V, V, P(ctypes.c_float), P(I)]
     lib.accept_decompress_timed.argtypes = [P(Desc), V, V, V, V, P(ctypes.c_float), P(I)]
@@ -65,7 +66,7 @@ def _load():
     lib.accept_version.argtypes = []
     lib.accept_version.restype = ctypes.c_char_p
     for name in ("accept_packed_size", "accept_workspace_size", "accept_compress", "accept_decompress",
-                 "accept_mbq_init", "accept_compress_timed", "accept_decompress_timed"):
+                 "accept_compress_noalloc", "accept_mbq_init", "accept_compress_timed", "accept_decompress_timed"):
         getattr(lib, name).restype = I
     return lib
 
@@ -160,6 +161,15 @@ def accept_compress(desc, x, alpha_prev=None, header=None, payload=None, workspa
     st = lib.accept_compress(ctypes.byref(desc), _ptr(x), _ptr(alpha_prev), _ptr(header), _ptr(payload),
                              _ptr(workspace), _stream_handle())
     _check(st, "accept_compress")
+    return header, payload
+
+
+def accept_compress_noalloc(desc, x, alpha_prev, header, payload):
+    """accept_compress on the library's built-in scratch: the caller passes every buffer and
+    nothing is allocated, here or in the library."""
+    st = lib.accept_compress_noalloc(ctypes.byref(desc), _ptr(x), _ptr(alpha_prev), _ptr(header), _ptr(payload),
+                                     _stream_handle())
+    _check(st, "accept_compress_noalloc")
     return header, payload
 
 

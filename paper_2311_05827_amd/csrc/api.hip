@@ -2,6 +2,8 @@
 // launchers.  No device memory is allocated here and nothing is kept between calls.
 #include <string.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 using namespace accept;
@@ -10,6 +12,28 @@ namespace {
 
 constexpr int64_t kMaxElems = int64_t(1) << 40;
 constexpr int64_t kMaxChannels = int64_t(1) << 24;
+
+// Scratch of accept_compress_noalloc: one array per GPU, part of the loaded code object, so it
+// exists without any allocation call.  In host code the array's name is only a handle; the
+// device address comes from hipGetSymbolAddress, once per device, and is what the kernels get.
+constexpr size_t kScratchBytes = ACCEPT_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the current device's scratch array (looked up on first use), or null.
+void* scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -139,6 +163,18 @@ accept_status accept_decompress(const accept_desc* desc, const void* header_dev,
                                 void* xhat_dev, void* hip_stream) {
   hipError_t e;
   return do_decompress(desc, header_dev, payload_dev, xhat_dev, hip_stream, nullptr, &e);
+}
+
+accept_status accept_compress_noalloc(const accept_desc* desc, const void* x_dev, const float* alpha_prev_dev,
+                                      void* header_dev, void* payload_dev, void* hip_stream) {
+  const accept_status st = check_desc(desc);
+  if (st != ACCEPT_OK) return st;
+  const size_t need = desc->scheme == ACCEPT_UNIFORM ? make_uplan(*desc).bytes : make_mplan(*desc).bytes;
+  if (need > kScratchBytes) return ACCEPT_ERR_UNSUPPORTED;  // host-only check, before any HIP call
+  void* ws = scratch_of_current_device();
+  if (!ws) return ACCEPT_ERR_HIP;
+  hipError_t e;
+  return do_compress(desc, x_dev, alpha_prev_dev, header_dev, payload_dev, ws, hip_stream, nullptr, &e);
 }
 
 accept_status accept_mbq_init(const accept_desc* desc, const void* x_dev, float* alpha0_dev, void* workspace_dev,
