@@ -112,8 +112,9 @@ typedef struct {
  */
 accept_status accept_packed_size(const accept_desc* desc, size_t* header_bytes, size_t* payload_bytes);
 
-/* Bytes of device scratch accept_compress needs for this descriptor (host-only; always a
- * multiple of 256; depends on the descriptor alone, not on the device). */
+/* Bytes of device scratch accept_compress, accept_mbq_init and accept_mbq_compress_first need
+ * for this descriptor (host-only; always a multiple of 256; depends on the descriptor alone,
+ * not on the device).  See accept_compress for how the workspace is to be prepared. */
 accept_status accept_workspace_size(const accept_desc* desc, size_t* bytes);
 
 /*
@@ -130,11 +131,16 @@ accept_status accept_workspace_size(const accept_desc* desc, size_t* bytes);
  *     residue initialisation).  One pass assigns every element to its nearest level,
  *     writes the bit planes (byte ((g*m + j)*k + p), g = row/8, holds bit p of rows
  *     8g..8g+7 of column j, first row in the most significant bit, rows >= n as 0) and
- *     accumulates the least-squares sums; a second tiny kernel writes
- *     header = [alpha_t, m_q].  Feed header[0..k) back as alpha_prev of the next batch.
+ *     accumulates the least-squares sums; the workgroup that finishes last solves for
+ *     alpha_t and writes header = [alpha_t, m_q] (one kernel in all).  Feed header[0..k)
+ *     back as alpha_prev of the next batch.
  *
- * workspace_dev: accept_workspace_size bytes, 256-byte aligned, contents arbitrary on
- * entry and undefined on return.  Calls that share a workspace must not overlap.
+ * workspace_dev: accept_workspace_size bytes, 256-byte aligned.  Zero-fill it once after
+ * allocating it (hipMemset); from then on the library keeps it in the state its next call
+ * needs (its first 256 bytes hold counters that every kernel leaves at zero; the rest is
+ * scratch whose contents do not matter), so one workspace serves any number of calls and
+ * descriptors of both schemes, one call at a time: calls that share a workspace must not
+ * overlap.
  * hip_stream: a hipStream_t (null = the default stream).
  */
 accept_status accept_compress(const accept_desc* desc, const void* x_dev, const float* alpha_prev_dev,
@@ -161,8 +167,9 @@ accept_status accept_decompress(const accept_desc* desc, const void* header_dev,
  * with ACCEPT_ERR_UNSUPPORTED before any HIP call (every MBQ descriptor and every per-tensor
  * UNIFORM descriptor fits; per-channel ones fit up to about 250,000 (row, channel) segments).
  * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
- * (different streams or threads) race; calls on one stream are safe.  Nothing in the array has
- * to start at zero (the kernels write what they later read), so no clearing is enqueued.
+ * (different streams or threads) race; calls on one stream are safe.  The array starts
+ * zero-filled when the library is loaded and every kernel leaves its counters at zero, which
+ * is all the kernels rely on, so no clearing is enqueued.
  */
 enum { ACCEPT_NOALLOC_SCRATCH_BYTES = 1 << 20 };
 accept_status accept_compress_noalloc(const accept_desc* desc, const void* x_dev, const float* alpha_prev_dev,
@@ -178,12 +185,25 @@ accept_status accept_mbq_init(const accept_desc* desc, const void* x_dev, float*
                               void* workspace_dev, void* hip_stream);
 
 /*
+ * Compression of batch 0 of an epoch (paragraph "Forward Quantizer": at batch 0 B^0 and
+ * alpha^0 come from the residue method and are what is sent; the search among the levels of
+ * the previous batch starts at batch 1).  Writes payload = the bit planes of B^0 (b_j =
+ * sign(rho_j), layout as accept_compress) and header = [alpha^0, m_q] with m_q =
+ * mean(B^0 alpha^0 - x) (eq. (biased error)); accept_decompress reads them like any other
+ * batch, and header[0..k) is alpha_prev of batch 1.  k passes over x (alpha_j needs the whole
+ * tensor's |rho_j|); the last one also writes the planes.  MBQ descriptors with
+ * ACCEPT_LAYOUT_PACKED only; desc->t is ignored; buffers and workspace as for accept_compress.
+ */
+accept_status accept_mbq_compress_first(const accept_desc* desc, const void* x_dev, void* header_dev,
+                                        void* payload_dev, void* workspace_dev, void* hip_stream);
+
+/*
  * Measurement variants: same work as accept_compress / accept_decompress, but every
  * kernel the call launches is bracketed by HIP events on the given stream; the call then
  * WAITS for the last event and writes each stage's duration in milliseconds to the host
  * array stage_ms[0..*n_stages) (capacity ACCEPT_MAX_STAGES).  Stage order:
- *   UNIFORM compress: range, [range finalize], quantize+pack;   MBQ compress: encode+sums,
- *   finalize;   decompress: the one kernel.
+ *   UNIFORM compress: range, [range finalize], quantize+pack;   MBQ compress: the one kernel;
+ *   decompress: the one kernel.
  * For benchmarks only; creates and destroys its events on every call.
  */
 enum { ACCEPT_MAX_STAGES = 8 };

@@ -482,3 +482,31 @@ def mbq_residue_init(x, k):
         alpha[j] = a
         rho = rho - np.where(pos, np.float64(a), -np.float64(a))
     return alpha, code
+
+
+def mbq_compress_first(x, k, n, m, in_bf16=False):
+    """Batch 0 of an epoch ("Forward Quantizer": B^0 and alpha^0 come from the residue method and
+    are what is transmitted; the search among the previous batch's levels starts at batch 1).
+    Header [alpha^0 (k floats), m_q] with m_q = mean(B^0 alpha^0 - x) (eq. (biased error)),
+    payload = the bit planes of B^0 ("Forward Encoder")."""
+    x32 = _as_f32(x, in_bf16)
+    N = int(n) * int(m)
+    alpha0, code = mbq_residue_init(x32, k)
+    _, _, Sb, Sx = mbq_stats(x32, code, k)
+    mq = mbq_mean_error(alpha0, Sb, Sx, N)
+    header = np.concatenate([alpha0, np.array([mq], dtype=F32)]).astype("<f4").tobytes()
+    return header, mbq_pack(code, k, n, m)
+
+
+def mbq_residue_signs(x, alpha):
+    """The sign patterns of the residue method for GIVEN coefficients: b_j = sign(rho_j)
+    (sign(0) = +1), rho_0 = x, rho_(j+1) = rho_j - alpha_j b_j, in float64 like
+    mbq_residue_init.  (With alpha = mbq_residue_init's own alpha^0 this is its B^0.)"""
+    alpha = np.asarray(alpha, dtype=F32).reshape(-1)
+    rho = np.asarray(x, dtype=F32).reshape(-1).astype(np.float64)
+    code = np.zeros(rho.size, dtype=np.int64)
+    for j in range(alpha.size):
+        pos = rho >= 0.0
+        code |= pos.astype(np.int64) << j
+        rho = rho - np.where(pos, np.float64(alpha[j]), -np.float64(alpha[j]))
+    return code

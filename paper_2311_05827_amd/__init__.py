@@ -9,7 +9,7 @@ import importlib
 
 _BINDING_NAMES = (
     "Desc", "make_desc", "AcceptError", "accept_packed_size", "accept_workspace_size", "accept_compress",
-    "accept_decompress", "accept_compress_noalloc", "accept_mbq_init", "accept_compress_timed", "accept_decompress_timed",
+    "accept_decompress", "accept_compress_noalloc", "accept_mbq_init", "accept_mbq_compress_first", "accept_compress_timed", "accept_decompress_timed",
     "accept_bits_schedule", "accept_stage_name", "alloc_outputs", "dtype_code", "status_string", "version",
     "UNIFORM", "MBQ", "F32", "BF16", "ROUND_NEAREST_EVEN", "ROUND_STOCHASTIC",
     "LAYOUT_PACKED", "LAYOUT_BATCH", "LAYOUT_UNENCODED",

@@ -55,6 +55,7 @@ def _load():
     lib.accept_decompress.argtypes = [P(Desc), V, V, V, V]
     lib.accept_compress_noalloc.argtypes = [P(Desc), V, V, V, V, V]
     lib.accept_mbq_init.argtypes = [P(Desc), V, V, V, V]
+    lib.accept_mbq_compress_first.argtypes = [P(Desc), V, V, V, V, V]
     lib.accept_compress_timed.argtypes = [P(Desc), V, V, V, V, V, V, P(ctypes.c_float), P(I)]
     lib.accept_decompress_timed.argtypes = [P(Desc), V, V, V, V, P(ctypes.c_float), P(I)]
     lib.accept_stage_name.argtypes = [P(Desc), I, I]
@@ -66,7 +67,7 @@ def _load():
     lib.accept_version.argtypes = []
     lib.accept_version.restype = ctypes.c_char_p
     for name in ("accept_packed_size", "accept_workspace_size", "accept_compress", "accept_decompress",
-                 "accept_compress_noalloc", "accept_mbq_init", "accept_compress_timed", "accept_decompress_timed"):
+                 "accept_compress_noalloc", "accept_mbq_init", "accept_mbq_compress_first", "accept_compress_timed", "accept_decompress_timed"):
         getattr(lib, name).restype = I
     return lib
 
@@ -138,13 +139,14 @@ def dtype_code(t):
 
 
 def alloc_outputs(desc, device):
-    """header (uint8, 4-byte sized), payload (uint8) and workspace (uint8) device buffers."""
+    """header (uint8, 4-byte sized), payload (uint8) and workspace (uint8, zero-filled as the
+    library asks of a fresh workspace) device buffers."""
     torch = _torch()
     hb, pb = accept_packed_size(desc)
     wb = accept_workspace_size(desc)
     header = torch.empty(hb, dtype=torch.uint8, device=device)
     payload = torch.empty(max(pb, 1), dtype=torch.uint8, device=device)[:pb]
-    workspace = torch.empty(wb, dtype=torch.uint8, device=device)
+    workspace = torch.zeros(wb, dtype=torch.uint8, device=device)
     return header, payload, workspace
 
 
@@ -189,10 +191,23 @@ def accept_mbq_init(desc, x, alpha0=None, workspace=None):
     if alpha0 is None:
         alpha0 = torch.empty(desc.bits, dtype=torch.float32, device=x.device)
     if workspace is None:
-        workspace = torch.empty(accept_workspace_size(desc), dtype=torch.uint8, device=x.device)
+        workspace = torch.zeros(accept_workspace_size(desc), dtype=torch.uint8, device=x.device)
     st = lib.accept_mbq_init(ctypes.byref(desc), _ptr(x), _ptr(alpha0), _ptr(workspace), _stream_handle())
     _check(st, "accept_mbq_init")
     return alpha0
+
+
+def accept_mbq_compress_first(desc, x, header=None, payload=None, workspace=None):
+    """Batch 0 of an epoch: residue initialisation; returns (header, payload) like accept_compress."""
+    if header is None or payload is None or workspace is None:
+        h, p, w = alloc_outputs(desc, x.device)
+        header = h if header is None else header
+        payload = p if payload is None else payload
+        workspace = w if workspace is None else workspace
+    st = lib.accept_mbq_compress_first(ctypes.byref(desc), _ptr(x), _ptr(header), _ptr(payload), _ptr(workspace),
+                                       _stream_handle())
+    _check(st, "accept_mbq_compress_first")
+    return header, payload
 
 
 def accept_compress_timed(desc, x, alpha_prev, header, payload, workspace):

@@ -7,8 +7,8 @@ batch and wires it into PyTorch:
 * the adaptive bit widths (forward 2 -> 3 -> 4, one step per learning-rate change; backward
   8 -> 4 at the first change; paragraphs after eq. (biased error) and after the
   stochastic-rounding equation),
-* the multi-bit coefficients alpha and the batch index t of eq. (alpha update), with the
-  residue initialisation at batch 0 of every epoch (paragraph "Forward Quantizer"),
+* the multi-bit coefficients alpha and the batch index t of eq. (alpha update); batch 0 of
+  every epoch is compressed by the residue method itself (paragraph "Forward Quantizer"),
 * the straight-through estimator for the quantizer's gradient (the equation after the
   bit-width paragraph): the backward pass hands the gradient on unchanged, or, when a
   backward compressor is given, after its own uniform compress/decompress round trip, as it
@@ -67,8 +67,11 @@ class ForwardCompressor:
             self._bufs = B.alloc_outputs(d, x.device)
         header, payload, ws = self._bufs
         if self.alpha is None:
-            self.alpha = B.accept_mbq_init(d, x, workspace=ws)
-        B.accept_compress(d, x, alpha_prev=self.alpha, header=header, payload=payload, workspace=ws)
+            # batch 0 of an epoch: B^0 and alpha^0 of the residue method are what is sent; the
+            # search among the previous batch's levels starts with the next batch
+            B.accept_mbq_compress_first(d, x, header=header, payload=payload, workspace=ws)
+        else:
+            B.accept_compress(d, x, alpha_prev=self.alpha, header=header, payload=payload, workspace=ws)
         self.alpha = header[: 4 * k].view(_torch().float32).clone()
         self.t += 1
         return d, header, payload

@@ -25,6 +25,9 @@ HIPCC_FLAGS = [
     "-ffp-contract=off",           # the quantizer's multiply and add must stay two roundings
     "-fno-gpu-flush-denormals-to-zero",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # The encoder's work-queue atomic is issued by one lane and its answer is looked at an item
+    # later; the atomic optimizer would rewrite it into a form that waits for the answer at once.
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
     "-I", os.path.join(ROOT, "include"),
     "-I", CSRC,

@@ -185,7 +185,22 @@ accept_status accept_mbq_init(const accept_desc* desc, const void* x_dev, float*
   if (!x_dev || !alpha0_dev || !workspace_dev) return ACCEPT_ERR_INVALID_ARG;
   if (!aligned(x_dev, 16) || !aligned(alpha0_dev, 4) || !aligned(workspace_dev, 256)) return ACCEPT_ERR_INVALID_ARG;
   const MPlan p = make_mplan(*desc);
-  const hipError_t e = launch_mbq_init(*desc, p, x_dev, alpha0_dev, workspace_dev, static_cast<hipStream_t>(hip_stream));
+  const hipError_t e =
+      launch_mbq_init(*desc, p, x_dev, alpha0_dev, nullptr, workspace_dev, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? ACCEPT_OK : ACCEPT_ERR_HIP;
+}
+
+accept_status accept_mbq_compress_first(const accept_desc* desc, const void* x_dev, void* header_dev,
+                                        void* payload_dev, void* workspace_dev, void* hip_stream) {
+  const accept_status st = check_desc(desc);
+  if (st != ACCEPT_OK) return st;
+  if (desc->scheme != ACCEPT_MBQ || desc->layout != ACCEPT_LAYOUT_PACKED) return ACCEPT_ERR_INVALID_ARG;
+  if (!x_dev || !header_dev || !payload_dev || !workspace_dev) return ACCEPT_ERR_INVALID_ARG;
+  if (!aligned(x_dev, 16) || !aligned(payload_dev, 16) || !aligned(header_dev, 4) || !aligned(workspace_dev, 256))
+    return ACCEPT_ERR_INVALID_ARG;
+  const MPlan p = make_mplan(*desc);
+  const hipError_t e = launch_mbq_init(*desc, p, x_dev, static_cast<float*>(header_dev), payload_dev, workspace_dev,
+                                       static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? ACCEPT_OK : ACCEPT_ERR_HIP;
 }
 

@@ -44,6 +44,12 @@ inline void mark(StageTimer* t, hipStream_t s) {
   if (t) t->mark(s);
 }
 
+// Every workspace starts with a control block that the library keeps between calls: words that
+// must be zero when a call starts and are put back to zero before it ends (the work counters of
+// the multi-bit encoder).  The caller zero-fills the workspace once; no kernel of either scheme
+// writes anything else there.
+constexpr size_t kCtrlBytes = 16384;
+
 // ---- scheme U (uniform) -----------------------------------------------------------------
 enum UMode { U_TENSOR = 0, U_SEGMENTED = 1, U_GENERIC = 2 };
 
@@ -69,11 +75,14 @@ hipError_t launch_uniform_decompress(const accept_desc& d, const void* header, c
 
 // ---- scheme M (multi-bit) ---------------------------------------------------------------
 struct MPlan {
-  int vec;          // columns per work item: 16-byte vectors when rows stay 16-byte aligned, else 1
-  int64_t G;        // ceil(n/8) row groups
-  int64_t items;    // G * (m / vec)
-  int grid;         // workgroups of the encode kernel = number of partial-sum records
-  int nstat;        // doubles per record
+  int vec;                // columns per work item: 16-byte vectors when rows stay 16-byte aligned, else 1
+  int64_t G;              // ceil(n/8) row groups
+  int64_t items;          // G * (m / vec)
+  bool stream;            // complete row groups go through the pipelined wave-item stream
+  uint32_t wpg;           // wave-items (64 items) per row group
+  uint32_t n_wave_items;  // of the complete row groups
+  int grid;               // workgroups of the encode kernel = number of partial-sum records
+  int nstat;              // doubles per record
   size_t bytes;
 };
 
@@ -83,8 +92,8 @@ hipError_t launch_mbq_compress(const accept_desc& d, const MPlan& p, const void*
                                void* header, void* payload, void* ws, hipStream_t s, StageTimer* tm);
 hipError_t launch_mbq_decompress(const accept_desc& d, const void* header, const void* payload, void* xhat,
                                  hipStream_t s, StageTimer* tm);
-hipError_t launch_mbq_init(const accept_desc& d, const MPlan& p, const void* x, float* alpha0, void* ws,
-                           hipStream_t s);
+hipError_t launch_mbq_init(const accept_desc& d, const MPlan& p, const void* x, float* alpha_out, void* payload,
+                           void* ws, hipStream_t s);
 
 // ---- device helpers ---------------------------------------------------------------------
 #if defined(__HIPCC__)
@@ -240,11 +249,41 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// Sum over the 64 lanes in a fixed butterfly order (deterministic); all lanes get the sum.
+// Lane exchange of a float64 inside a row of 16 lanes (two 32-bit DPP moves).
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const uint64_t b = uint64_t(__double_as_longlong(v));
+  const uint32_t lo = dpp_u32<CTRL>(uint32_t(b)), hi = dpp_u32<CTRL>(uint32_t(b >> 32));
+  return __longlong_as_double((long long)((uint64_t(hi) << 32) | lo));
+}
+__device__ __forceinline__ double readlane_f64(double v, int lane) {
+  const uint64_t b = uint64_t(__double_as_longlong(v));
+  const uint32_t lo = uint32_t(__builtin_amdgcn_readlane(int(uint32_t(b)), lane));
+  const uint32_t hi = uint32_t(__builtin_amdgcn_readlane(int(uint32_t(b >> 32)), lane));
+  return __longlong_as_double((long long)((uint64_t(hi) << 32) | lo));
+}
+
+// Sum over the 64 lanes in a fixed order (so the result does not depend on timing); every lane
+// receives the same value.  Four butterfly steps inside each row of 16 lanes (partners add in
+// either order: the same float64 either way), then the four row sums as (r0 + r1) + (r2 + r3).
 __device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
-  return v;
+  v += dpp_f64<kDppQuadSwap1>(v);
+  v += dpp_f64<kDppQuadSwap2>(v);
+  v += dpp_f64<kDppRowHalfMirror>(v);
+  v += dpp_f64<kDppRowMirror>(v);
+  const double r0 = readlane_f64(v, 0), r1 = readlane_f64(v, 16), r2 = readlane_f64(v, 32), r3 = readlane_f64(v, 48);
+  return (r0 + r1) + (r2 + r3);
+}
+
+// Loads and stores that are coherent across the whole device although every group of compute
+// units has a second-level cache of its own: they go through to memory instead of staying in
+// (or being served from) that cache.  For the few words workgroups hand to each other inside
+// one kernel.
+__device__ __forceinline__ void store_device_scope(double* p, double v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double load_device_scope(const double* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // u in [0,1) on a 2^-24 grid: top 24 bits of splitmix64's output function at

@@ -15,23 +15,25 @@ namespace accept {
 
 namespace {
 
-// Launch-shape constants; the -D overrides exist for tuning sweeps only.
-#ifndef ACCEPT_ENCODE_GRID
-#define ACCEPT_ENCODE_GRID 768
-#endif
-#ifndef ACCEPT_ENCODE_WAVES
-#define ACCEPT_ENCODE_WAVES 2  // wavefronts per SIMD the encode kernel is compiled for
-#endif
-#ifndef ACCEPT_ENCODE_GROUP
-#define ACCEPT_ENCODE_GROUP 4  // elements whose table lookups are issued together (at least one row)
-#endif
-#ifndef ACCEPT_DECODE_GRID
-#define ACCEPT_DECODE_GRID 8192
-#endif
-constexpr int kEncodeGridMax = ACCEPT_ENCODE_GRID;  // also the number of partial-sum records
-constexpr int kDecodeGridMax = ACCEPT_DECODE_GRID;
+// Launch shapes.  The bit-plane encoder runs one workgroup of 8 wavefronts per compute unit
+// (256 on this chip): the wavefronts of a compute unit share one set of tables in local memory.
+// The comparison-layout encoder and the residue pass are plain 256-thread kernels.
+constexpr int kEncBlock = 512;
+constexpr int kEncWaves = kEncBlock / kWave;
+// Wavefronts draw their work from counters in device memory; the workgroups with block indices
+// 8i .. 8i+7 (under round-robin dispatch one on each of the chip's eight dies) share counter i.
+constexpr int kGroupBlocks = 8;
+constexpr int kGroupSlots = 64;     // wave-items a group takes out of every sweep over the tensor
+constexpr int kCounterStride = 64;  // uint32 words between two counters (256 bytes: their own cache lines)
+constexpr int kEncodeGridMax = 256;
+constexpr int kPlainGridMax = 768;
+constexpr int kDecodeGridMax = 8192;
 constexpr int kInitGrid = 1024;
-static_assert(kEncodeGridMax <= 2048, "the workspace holds at most 2048 records");
+constexpr int kMaxRecords = 2048;  // per-workgroup records the workspace has room for
+constexpr int kMaxWaves = 16;      // wavefronts of the largest workgroup
+constexpr int kMaxGroups = kEncodeGridMax / kGroupBlocks;
+static_assert(size_t(kMaxGroups) * kCounterStride * sizeof(uint32_t) <= kCtrlBytes, "the control block holds the counters");
+static_assert(kEncodeGridMax <= kMaxRecords && kPlainGridMax <= kMaxRecords && kInitGrid <= kMaxRecords, "records");
 
 template <int NDW>
 struct alignas((NDW % 4 == 0) ? 16 : (NDW % 2 == 0) ? 8 : 4) Dwords {
@@ -57,17 +59,14 @@ __device__ __forceinline__ void item_advance(ItemPos& p, const ItemStep& st, int
 // ascending with ties by pattern.  Thread `pat` computes its level and its rank; on return
 // lv_sorted[rank] and pat_sorted[rank] are filled (after the caller's barrier).
 template <int K>
-__device__ __forceinline__ void build_levels(const float* __restrict__ alpha, float* lv_raw, float* lv_sorted,
+__device__ __forceinline__ void build_levels(const float (&alpha)[K], float* lv_raw, float* lv_sorted,
                                              uint32_t* pat_sorted) {
   constexpr int P = 1 << K;
   const int pat = threadIdx.x;
   float lv = 0.0f;
   if (pat < P) {
 #pragma unroll
-    for (int j = 0; j < K; ++j) {
-      const float a = alpha[j];
-      lv = __fadd_rn(lv, ((pat >> j) & 1) ? a : -a);
-    }
+    for (int j = 0; j < K; ++j) lv = __fadd_rn(lv, ((pat >> j) & 1) ? alpha[j] : -alpha[j]);
     lv_raw[pat] = lv;
   }
   __syncthreads();
@@ -91,10 +90,7 @@ __device__ __forceinline__ void build_levels(const float* __restrict__ alpha, fl
 // thresholds that fall inside any one bucket (1 for well separated levels) and tau is padded
 // with +inf.  The float compares decide; the table only says where to start, so the result is
 // exactly #{i : x > tau_i}.
-#ifndef ACCEPT_LUT_BITS
-#define ACCEPT_LUT_BITS 12
-#endif
-constexpr int kLutBits = ACCEPT_LUT_BITS;
+constexpr int kLutBits = 12;
 constexpr int kLutSize = 1 << kLutBits;
 
 template <int K>
@@ -123,126 +119,178 @@ __device__ __forceinline__ float bucket_vmin(int b) {
   return u32_as_f32((b >> (kLutBits - 1)) ? hi_bits : lo_bits);
 }
 
-template <int K>
-__device__ __forceinline__ void build_encode_tables(const float* __restrict__ alpha_prev, EncodeTables<K>& tb) {
-  using TB = EncodeTables<K>;
-  constexpr int P = TB::P;
-  constexpr int PER = kLutSize / kBlock;  // consecutive buckets per thread
-  static_assert(kLutSize % (4 * kBlock) == 0, "each thread writes whole dwords of the bucket table");
-  const int tid = threadIdx.x;
-  if (tid == 0) tb.maxcnt = 1;
-  build_levels<K>(alpha_prev, tb.lv_raw, tb.lv_sorted, tb.pat_sorted);
-  for (int i = tid; i < 3 * P; i += kBlock)
-    tb.tau[i] = (i < P - 1) ? __fmul_rn(0.5f, __fadd_rn(tb.lv_sorted[i], tb.lv_sorted[i + 1])) : __builtin_inff();
-  if (tid < P) {
-    const uint32_t pat = tb.pat_sorted[tid];
-#pragma unroll
-    for (int w = 0; w < TB::NW; ++w) {
-      uint32_t sp = 0;
-#pragma unroll
-      for (int bb = 0; bb < 4; ++bb)
-        if (4 * w + bb < K) sp |= ((pat >> (4 * w + bb)) & 1u) << (8 * bb);
-      tb.spread[tid * TB::NW + w] = sp;
+
+// The bucket table and the largest number of thresholds inside one bucket.
+//   lo(b) = #{tau_i < smallest value of bucket b}, through `count_below(value)`;
+//   thresholds inside bucket b = lo(value-order successor of b) - lo(b).  The successor is b+1 on
+//   the positive side (b < kLutSize/2) and b-1 on the negative side, where bucket kLutSize/2 (-0)
+//   is followed by bucket 0.  Buckets of NaN bit patterns give differences <= 0: ignored.
+// A thread takes CH = 8 consecutive buckets (two dwords of the table; never across the sign
+// boundary).  lo is monotone along a side, and with a few thresholds among 4096 buckets almost
+// every chunk has the same lo at both ends: then every bucket of it has that lo and no threshold
+// inside, and only the step to the chunk's successor bucket is left to look at.  The few chunks
+// with a threshold inside are then redone one after the other by the whole wavefront, lane j
+// taking bucket j of the chunk (one evaluation per chunk instead of eight in a row by one lane).
+template <int SHIFT, typename F>
+__device__ __forceinline__ int build_bucket_table(uint8_t* lut, F count_below) {
+  constexpr int CH = 8;
+  static_assert(kLutSize % (2 * CH) == 0, "chunks stay on one side of the sign boundary");
+  static_assert((kLutSize / CH) % kWave == 0, "all lanes of a wavefront run the same number of rounds");
+  uint32_t* lut32 = reinterpret_cast<uint32_t*>(lut);
+  const int lane = threadIdx.x & (kWave - 1);
+  int mymax = 0;
+#pragma nounroll
+  for (int b0 = threadIdx.x * CH; b0 < kLutSize; b0 += blockDim.x * CH) {
+    const bool neg = b0 >= kLutSize / 2;
+    // the chunk's first and last bucket in value order, and the bucket that follows the last
+    const int b_first = neg ? b0 + CH - 1 : b0;
+    const int b_last = neg ? b0 : b0 + CH - 1;
+    int b_succ = neg ? b0 - 1 : b0 + CH;
+    if (neg && b0 == kLutSize / 2) b_succ = 0;                  // -0's bucket is followed by +0's
+    const bool has_succ = neg || b0 + CH < kLutSize / 2;        // the top positive buckets hold NaN patterns
+    const int lo_first = count_below(bucket_vmin(b_first));
+    const int lo_last = count_below(bucket_vmin(b_last));
+    const int lo_succ = has_succ ? count_below(bucket_vmin(b_succ)) : lo_last;
+    const bool steps_inside = lo_first != lo_last;
+    if (!steps_inside) {
+      const int cnt = lo_succ - lo_last;
+      mymax = cnt > mymax ? cnt : mymax;
+    }
+    const uint32_t fill = (uint32_t(lo_first) * 0x01010101u) << SHIFT;  // lo < 32 when shifted by 3: no carry between bytes
+    lut32[b0 / 4] = fill;
+    lut32[b0 / 4 + 1] = fill;
+    // chunks with a threshold inside (their entries were just filled with a placeholder)
+    uint64_t pending = __ballot(steps_inside);
+    while (pending != 0) {  // the same in every lane
+      const int src = __ffsll((unsigned long long)pending) - 1;
+      pending &= pending - 1;
+      const int cb0 = __builtin_amdgcn_readlane(b0, src);
+      const int c_succ = __builtin_amdgcn_readlane(lo_succ, src);
+      const bool cneg = cb0 >= kLutSize / 2;
+      const int j = lane & (CH - 1);  // lanes 8.. repeat the work of lanes 0..7 (and store the same bytes)
+      const int lo_j = count_below(bucket_vmin(cb0 + j));
+      lut[cb0 + j] = uint8_t(uint32_t(lo_j) << SHIFT);
+      // thresholds inside bucket cb0 + j: lo of its successor (inside the chunk, else the chunk's) minus its own
+      const int lo_up = __shfl(lo_j, (lane & ~(CH - 1)) | ((j + 1) & (CH - 1)), kWave);
+      const int lo_down = __shfl(lo_j, (lane & ~(CH - 1)) | ((j + CH - 1) & (CH - 1)), kWave);
+      const int next = cneg ? (j > 0 ? lo_down : c_succ) : (j < CH - 1 ? lo_up : c_succ);
+      const int cnt = next - lo_j;
+      mymax = cnt > mymax ? cnt : mymax;
     }
   }
-  __syncthreads();
-  if (K <= 4 && tid <= P + 1) {
-    tb.pair[2 * tid] = f32_as_u32(tb.tau[tid]);                  // tau[P-1], tau[P], tau[P+1] are +inf
-    tb.pair[2 * tid + 1] = tid < P ? tb.spread[tid] : 0u;
-  }
-  // lo(b) = #{tau_i < smallest value of bucket b}.  tau[0..P-1) is sorted and tau[P-1] = +inf, so a
-  // branch-free binary search over P entries finds it.  A thread owns PER consecutive buckets
-  // (one more is evaluated for the count below) and writes them four to a dword.
-  // Thresholds inside bucket b = lo(value-order successor of b) - lo(b); the successor is b+1 on
-  // the positive side and b-1 on the negative side (bucket kLutSize/2 is followed by bucket 0).
-  // Buckets of NaN bit patterns get lo = 0, which makes their differences <= 0: ignored.
+  return mymax;
+}
+
+// M1 and the search tables.  alpha[0..K) = the previous coefficients, already in registers (the
+// caller loads them first thing, so that their trip to memory overlaps its other set-up work).
+template <int K>
+__device__ __forceinline__ void build_encode_tables(const float (&alpha)[K], EncodeTables<K>& tb) {
+  using TB = EncodeTables<K>;
+  constexpr int P = TB::P;
+  const int tid = threadIdx.x;
+  const int nthr = blockDim.x;  // at least P = 256 for K = 8
   int mymax = 0;
-  uint32_t* lut32 = reinterpret_cast<uint32_t*>(tb.lut);
-  constexpr int CH = 8;  // buckets per step: bounds the registers this prologue needs
-  static_assert(PER % CH == 0, "bucket chunks");
-#pragma nounroll
-  for (int c0 = 0; c0 < PER; c0 += CH) {
-    const int b0 = tid * PER + c0;
-    const bool neg = b0 >= kLutSize / 2;
-    int lo[CH + 2];  // lo[j+1] belongs to bucket b0 + j; lo[0] and lo[CH+1] are the neighbours
+  if (tid == 0) tb.maxcnt = 1;
+  if constexpr (K <= 4) {
+    // Few levels: the first wavefront sorts them in registers, lane p holding pattern p.  Its rank
+    // is the number of levels below its own (ties by pattern); a lane-to-lane push then hands
+    // every level to the lane of its rank, and thresholds, spread patterns and the pair table
+    // follow without a barrier.
+    if (tid < kWave) {
+      const int pat = tid;
+      float lv = 0.0f;
 #pragma unroll
-    for (int j = -1; j <= CH; ++j) {
-      int b = b0 + j;
-      if (b < 0) b = kLutSize / 2;          // predecessor of bucket 0 in value order is -0's bucket
-      if (b >= kLutSize) b = kLutSize - 1;  // no bucket beyond the last: reuse it (difference 0)
-      const float vmin = bucket_vmin(b);
+      for (int j = 0; j < K; ++j) lv = __fadd_rn(lv, ((pat >> j) & 1) ? alpha[j] : -alpha[j]);
+      int rank = 0;
+#pragma unroll
+      for (int q = 0; q < P; ++q) {
+        const float o = u32_as_f32(uint32_t(__builtin_amdgcn_readlane(int(f32_as_u32(lv)), q)));
+        rank += (o < lv || (o == lv && q < pat)) ? 1 : 0;
+      }
+      if (pat >= P) rank = pat;  // idle lanes push to themselves
+      const float lv_s = u32_as_f32(uint32_t(__builtin_amdgcn_ds_permute(rank * 4, int(f32_as_u32(lv)))));
+      const uint32_t pat_s = uint32_t(__builtin_amdgcn_ds_permute(rank * 4, pat));
+      const float lv_next = u32_as_f32(uint32_t(__builtin_amdgcn_ds_bpermute(((tid + 1) & (kWave - 1)) * 4,
+                                                                            int(f32_as_u32(lv_s)))));
+      const float tau = tid < P - 1 ? __fmul_rn(0.5f, __fadd_rn(lv_s, lv_next)) : __builtin_inff();
+      uint32_t sp = 0;
+#pragma unroll
+      for (int bb = 0; bb < K; ++bb) sp |= ((pat_s >> bb) & 1u) << (8 * bb);
+      if (tid < 3 * P) tb.tau[tid] = tau;  // 3P <= 48 lanes: thresholds, then +inf padding
+      if (tid < P) {
+        tb.lv_sorted[tid] = lv_s;
+        tb.pat_sorted[tid] = pat_s;
+        tb.spread[tid] = sp;
+      }
+      if (tid <= P + 1) {
+        tb.pair[2 * tid] = f32_as_u32(tau);  // tau[P-1], tau[P], tau[P+1] are +inf
+        tb.pair[2 * tid + 1] = tid < P ? sp : 0u;
+      }
+    }
+    __syncthreads();
+    // bucket table: the P-1 thresholds sit in registers, a bucket's lo is P-1 compares
+    float t[P - 1];
+#pragma unroll
+    for (int i = 0; i < P - 1; ++i) t[i] = tb.tau[i];
+    mymax = build_bucket_table<TB::LUT_SHIFT>(tb.lut, [&](float vmin) {
+      int l = 0;
+#pragma unroll
+      for (int i = 0; i < P - 1; ++i) l += (t[i] < vmin) ? 1 : 0;
+      return l;
+    });
+  } else {
+    build_levels<K>(alpha, tb.lv_raw, tb.lv_sorted, tb.pat_sorted);
+    for (int i = tid; i < 3 * P; i += nthr)
+      tb.tau[i] = (i < P - 1) ? __fmul_rn(0.5f, __fadd_rn(tb.lv_sorted[i], tb.lv_sorted[i + 1])) : __builtin_inff();
+    if (tid < P) {
+      const uint32_t pat = tb.pat_sorted[tid];
+#pragma unroll
+      for (int w = 0; w < TB::NW; ++w) {
+        uint32_t sp = 0;
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb)
+          if (4 * w + bb < K) sp |= ((pat >> (4 * w + bb)) & 1u) << (8 * bb);
+        tb.spread[tid * TB::NW + w] = sp;
+      }
+    }
+    __syncthreads();
+    // bucket table: tau[0..P-1) is sorted and tau[P-1] = +inf, so a branch-free binary search over
+    // P entries finds lo
+    mymax = build_bucket_table<TB::LUT_SHIFT>(tb.lut, [&](float vmin) {
       int l = 0;
 #pragma unroll
       for (int s = P >> 1; s >= 1; s >>= 1) l += (tb.tau[l + s - 1] < vmin) ? s : 0;
-      lo[j + 1] = l;
-    }
-#pragma unroll
-    for (int j = 0; j < CH; ++j) {
-      // positive side: the successor is the next bucket; negative side: the previous one, except
-      // that the -0 bucket (kLutSize/2) is followed by bucket 0: that pair is counted below
-      int cnt = neg ? lo[j] - lo[j + 1] : lo[j + 2] - lo[j + 1];
-      if (neg && b0 + j == kLutSize / 2) cnt = 0;
-      if (!neg && b0 + j == kLutSize / 2 - 1) cnt = 0;  // top positive bucket: NaN patterns, no successor
-      mymax = cnt > mymax ? cnt : mymax;
-    }
-    if (b0 == 0) {
-      // thresholds inside the -0 bucket: lo(bucket 0) - lo(bucket kLutSize/2); lo[0] is that bucket
-      const int cnt = lo[1] - lo[0];
-      mymax = cnt > mymax ? cnt : mymax;
-    }
-#pragma unroll
-    for (int j = 0; j < CH; j += 4)
-      lut32[(b0 + j) / 4] = (uint32_t(lo[j + 1]) | (uint32_t(lo[j + 2]) << 8) | (uint32_t(lo[j + 3]) << 16) |
-                             (uint32_t(lo[j + 4]) << 24))
-                            << TB::LUT_SHIFT;  // lo < 32 when shifted by 3: no carry between bytes
+      return l;
+    });
   }
   if (mymax > 1) atomicMax(&tb.maxcnt, mymax);
   __syncthreads();
 }
 
-// Sum of NS per-thread float64 values over the 256 threads of a workgroup, in a fixed order
-// (so the result does not depend on timing): the values go to local memory one statistic per
-// row, 16 threads per statistic add 16 consecutive entries each, one thread adds those 16
-// partial sums.  Far cheaper than NS butterflies of 64-bit lane exchanges.  buf holds
-// kStatChunk rows; more statistics than that take several passes.  On return thread s < NS
-// holds total s in its return value (other threads: unspecified).
-constexpr int kStatChunk = 16;
-struct StatScratch {
-  double v[kStatChunk][kBlock];
-  double part[kStatChunk][16];
+// Sum of NS per-thread float64 values over the threads of a workgroup, in a fixed order (so the
+// result does not depend on timing): every wavefront adds its 64 lanes with register-to-register
+// lane exchanges, lane 0 parks the NS wave totals in local memory, and thread s < NS adds the
+// wavefronts' totals of statistic s in wavefront order.  On return thread s < NS holds total s
+// (other threads: unspecified).  Ends with the buffer free for reuse after one more barrier.
+struct WaveTotals {
+  double v[kMaxWaves][48];  // nstat_of(8) = 45 statistics at most
 };
 template <int NS>
-__device__ __forceinline__ double block_sum_stats(const double (&sv)[NS], StatScratch& buf) {
-  static_assert(kBlock == 256, "16 threads x 16 entries per statistic");
+__device__ __forceinline__ double block_sum_stats(const double (&sv)[NS], WaveTotals& buf) {
+  static_assert(NS <= 48, "statistics per record");
   const int tid = threadIdx.x;
+  const int wave = tid / kWave, lane = tid & (kWave - 1);
+  const int nwaves = (blockDim.x + kWave - 1) / kWave;
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    const double t = wave_sum(sv[s]);
+    if (lane == 0) buf.v[wave][s] = t;
+  }
+  __syncthreads();
   double mine = 0.0;
-#pragma unroll
-  for (int c0 = 0; c0 < NS; c0 += kStatChunk) {
-    constexpr int kAll = kStatChunk;
-    const int nc = (NS - c0) < kAll ? (NS - c0) : kAll;
-    if (c0 > 0) __syncthreads();  // the previous pass has been read
-#pragma unroll
-    for (int s = 0; s < kAll; ++s)
-      if (c0 + s < NS) buf.v[s][tid] = sv[c0 + s];
-    __syncthreads();
-    {
-      const int s = tid >> 4, part = tid & 15;
-      if (s < nc) {
-        const double* src = &buf.v[s][part * 16];
-        double a = src[0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) a += src[i];
-        buf.part[s][part] = a;
-      }
-    }
-    __syncthreads();
-    if (tid >= c0 && tid < c0 + nc) {
-      const double* src = buf.part[tid - c0];
-      double a = src[0];
-#pragma unroll
-      for (int i = 1; i < 16; ++i) a += src[i];
-      mine = a;
-    }
+  if (tid < NS) {
+    mine = buf.v[0][tid];
+    for (int w = 1; w < nwaves; ++w) mine += buf.v[w][tid];
   }
   return mine;
 }
@@ -328,34 +376,14 @@ __device__ __forceinline__ void encode_group(const EncodeTables<K>& tb, const fl
 }
 
 // End of an item: bit counts from the finished plane bytes, payload store, float32 partial
-// sums (at most 8*VEC terms) folded into the thread's float64 sums.
+// sums (at most 8*VEC terms) folded into the thread's float64 sums.  A lane whose item lies
+// beyond its row group (the ragged end of the last wave-item of a group) carries a copy of the
+// group's last item: it stores the same bytes to the same place and counts nothing.
 template <int K, int VEC>
 __device__ __forceinline__ void finish_item(const uint32_t (&acc)[VEC][(K + 3) / 4], const float (&h32)[K], float sx32,
-                                            uint8_t* __restrict__ dst, EncodeStats<K>& st) {
+                                            uint8_t* __restrict__ dst, bool counts, EncodeStats<K>& st) {
   constexpr int NDW = (VEC * K + 3) / 4;
   constexpr int CW = (VEC + 3) / 4;
-  uint32_t pw[K][CW];  // plane bytes of all VEC columns, plane-major
-#pragma unroll
-  for (int p = 0; p < K; ++p) {
-#pragma unroll
-    for (int w = 0; w < CW; ++w) pw[p][w] = 0;
-#pragma unroll
-    for (int c = 0; c < VEC; ++c) pw[p][c / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (c % 4));
-  }
-  {
-    int pi = 0;
-#pragma unroll
-    for (int p = 0; p < K; ++p) {
-#pragma unroll
-      for (int w = 0; w < CW; ++w) st.cnt[p] += __popc(pw[p][w]);
-#pragma unroll
-      for (int q = p + 1; q < K; ++q) {
-#pragma unroll
-        for (int w = 0; w < CW; ++w) st.dis[pi] += __popc(pw[p][w] ^ pw[q][w]);
-        ++pi;
-      }
-    }
-  }
   // payload: byte ((g*m + j)*K + p); the item's VEC*K bytes are contiguous
   if constexpr (VEC > 1) {
     uint32_t out[NDW];
@@ -378,9 +406,37 @@ __device__ __forceinline__ void finish_item(const uint32_t (&acc)[VEC][(K + 3) /
 #pragma unroll
     for (int p = 0; p < K; ++p) dst[p] = uint8_t(acc[0][p / 4] >> (8 * (p % 4)));
   }
-  st.Sx += double(sx32);
+  // (selects, not a branch around the sums: with a branch the compiler moves the whole chain of
+  // per-element adds of the item behind it, to the end of the round, and every row of x then
+  // has to stay in registers until there)
+  const uint32_t keep = counts ? 0xFFFFFFFFu : 0u;
+  uint32_t pw[K][CW];  // plane bytes of all VEC columns, plane-major
 #pragma unroll
-  for (int p = 0; p < K; ++p) st.H[p] += double(h32[p]);
+  for (int p = 0; p < K; ++p) {
+#pragma unroll
+    for (int w = 0; w < CW; ++w) pw[p][w] = 0;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) pw[p][c / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (c % 4));
+#pragma unroll
+    for (int w = 0; w < CW; ++w) pw[p][w] &= keep;
+  }
+  {
+    int pi = 0;
+#pragma unroll
+    for (int p = 0; p < K; ++p) {
+#pragma unroll
+      for (int w = 0; w < CW; ++w) st.cnt[p] += __popc(pw[p][w]);
+#pragma unroll
+      for (int q = p + 1; q < K; ++q) {
+#pragma unroll
+        for (int w = 0; w < CW; ++w) st.dis[pi] += __popc(pw[p][w] ^ pw[q][w]);
+        ++pi;
+      }
+    }
+  }
+  st.Sx += double(counts ? sx32 : 0.0f);
+#pragma unroll
+  for (int p = 0; p < K; ++p) st.H[p] += double(counts ? h32[p] : 0.0f);
 }
 
 // One row's share of an item as it comes from memory: VEC elements in a 16-byte vector, or a
@@ -448,30 +504,85 @@ __device__ __forceinline__ void encode_column(const EncodeTables<K>& tb, const T
   for (int r = 0; r < 8; ++r)
 #pragma unroll
     for (int w = 0; w < NW; ++w) acc[0][w] = (acc[0][w] << 1) | (r < nrows ? sp[r][w] : 0u);
-  finish_item<K, 1>(acc, h32, sx32, payload + ((g * m + j) * K), st);
+  finish_item<K, 1>(acc, h32, sx32, payload + ((g * m + j) * K), true, st);
 }
 
-// The pipelined loop over whole rounds of the grid (every thread has an item in every round).
+// ---- the pipelined stream over complete row groups -------------------------------------------
+// Unit of work = wave-item: 64 adjacent items (one per lane) of one row group, i.e. 8 rows x
+// 64*VEC columns, every row a contiguous run in memory.  Wavefronts draw wave-items one at a
+// time: a wavefront that is served faster (the instruction arbiter favours the oldest wavefront
+// of a SIMD, some dies sit closer to the memory they happen to read) simply takes more of them,
+// and the whole grid finishes together instead of waiting for its slowest compute unit.  The
+// counters live in device memory, one per group of eight workgroups (one counter for the whole
+// grid would see a request every nanosecond; an atomic on one address takes about twelve).
+// Which wavefront ran which wave-item decides only the grouping of the float64 partial sums,
+// never a payload bit.
+//
+// Queue position c of group i is wave-item (c / 64) * sweep + 64 * i + c % 64, sweep = 64 *
+// groups: at any time the grid reads one contiguous stretch of each of eight rows (the pattern
+// memory likes best), the groups advancing through the tensor side by side.
+struct WorkQueue {
+  uint32_t* counter;  // the group's counter: zero when the kernel starts, put back by the finalize kernel
+  uint32_t first;     // 64 * group
+  uint32_t sweep;     // wave-items all groups take per sweep
+  uint32_t count;     // queue positions 0 .. count-1 exist
+  uint32_t drawn;     // positions handed out without the counter: two per wavefront of the group
+};
+__device__ __forceinline__ uint32_t queue_to_wave_item(uint32_t c, const WorkQueue& q) {
+  return (c / uint32_t(kGroupSlots)) * q.sweep + q.first + (c % uint32_t(kGroupSlots));
+}
+
+// Where a lane's item of a wave-item lives: the row group (the same in all lanes and kept in
+// scalar registers, so that a row load is "scalar base + 32-bit lane offset" and costs no vector
+// registers for its address) and the lane's own item number inside the group.
+struct ItemAddr {
+  uint32_t g;    // row group (scalar)
+  uint32_t jv;   // item inside the group, clamped to the last one
+  bool counts;   // false for the clamped copies that fill the ragged end of a row group
+};
+// Item of lane `lane` in wave-item w; wpg wave-items and ipg items per row group (both below
+// 2^32, checked on the host, as are the byte lengths of a row of x and of a row group's planes).
+__device__ __forceinline__ ItemAddr item_addr(uint32_t w, uint32_t wpg, uint32_t ipg, int lane) {
+  ItemAddr a;
+  a.g = uint32_t(__builtin_amdgcn_readfirstlane(int(w / wpg)));
+  a.jv = (w - a.g * wpg) * uint32_t(kWave) + uint32_t(lane);
+  a.counts = a.jv < ipg;
+  if (!a.counts) a.jv = ipg - 1u;
+  return a;
+}
+// Row 8g + r of the item: the base is formed from scalars only; lane_x = jv * VEC * sizeof(T).
+template <typename T, int VEC>
+__device__ __forceinline__ RawRow<VEC> load_row(const T* __restrict__ x, uint32_t g, uint64_t row_bytes, int r,
+                                                uint32_t lane_x) {
+  const char* base = reinterpret_cast<const char*>(x) + (uint64_t(g) * 8u + uint64_t(r)) * row_bytes;
+  return load_raw<T, VEC>(reinterpret_cast<const T*>(base + lane_x));
+}
+
 template <typename T, int K, int VEC, int MC>
-__device__ __forceinline__ void encode_rounds(const EncodeTables<K>& tb, const T* __restrict__ x,
-                                              uint8_t* __restrict__ payload, int64_t m, int64_t ipg, int64_t rounds,
-                                              ItemPos pos, const ItemStep& step, RawRow<VEC> (&fr)[8],
-                                              EncodeStats<K>& st) {
+__device__ __forceinline__ void encode_stream(const EncodeTables<K>& tb, const T* __restrict__ x,
+                                              uint8_t* __restrict__ payload, uint64_t m, uint32_t ipg, uint32_t wpg,
+                                              const WorkQueue& q, uint32_t cur, uint32_t nxt, ItemAddr ca,
+                                              RawRow<VEC> (&fr)[8], EncodeStats<K>& st) {
   constexpr int NW = (K + 3) / 4;
-  constexpr int GR = VEC >= ACCEPT_ENCODE_GROUP ? 1 : ACCEPT_ENCODE_GROUP / VEC;  // rows handled together
+  constexpr int GR = VEC >= 4 ? 1 : 4 / VEC;  // rows whose table lookups are issued together (at least 4 elements)
+  const int lane = threadIdx.x & (kWave - 1);
+  const uint64_t row_bytes = m * sizeof(T);
   // The first item's rows have had the whole table build to arrive.  Waiting for them here
   // (vmcnt 0, the other counters untouched) gives the loop an empty set of outstanding loads
   // on entry whatever code precedes it, so that the waits the compiler places inside the loop
   // are the ones its own steady state needs and no more.
   __builtin_amdgcn_s_waitcnt(0x0F70);
-  for (int64_t rd = 0; rd < rounds; ++rd) {
-    ItemPos npos = pos;
-    item_advance(npos, step, ipg);
-    // In the last round there is no next item: every lane then re-reads the first item of the
-    // tensor (valid, one cache line per row for the whole wavefront), so that the loads stay
-    // unconditional and the compiler can reuse the row registers in place.
-    if (rd + 1 >= rounds) { npos.g = 0; npos.jv = 0; }
-    const T* nxc = x + npos.g * 8 * m + npos.jv * VEC;
+  while (cur < q.count) {
+    // the wave-item after the next: asked for now, looked at when this item is done (the answer
+    // comes back in line with the row loads issued below, well before it is needed)
+    uint32_t after_v = 0;
+    if (lane == 0) after_v = __hip_atomic_fetch_add(q.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // When there is no next wave-item every lane re-reads the first item of the tensor (valid,
+    // one cache line per row for the whole wavefront), so that the loads stay unconditional and
+    // the compiler can reuse the row registers in place.
+    ItemAddr na;
+    na.g = 0; na.jv = 0; na.counts = false;
+    if (nxt < q.count) na = item_addr(queue_to_wave_item(nxt, q), wpg, ipg, lane);
     uint32_t acc[VEC][NW];
     float h32[K];
     float sx32 = 0.0f;
@@ -500,148 +611,40 @@ __device__ __forceinline__ void encode_rounds(const EncodeTables<K>& tb, const T
         for (int c = 0; c < VEC; ++c)
 #pragma unroll
           for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | sp[rr * VEC + c][w];
+      // The loads of the next item's rows go where this group's rows were: they may not be
+      // issued before the last use of those registers (else the compiler keeps a second set of
+      // row registers and copies it over at the end of the round, which also means waiting for
+      // all eight loads there).
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        // the lane offset passes through an empty asm, so that the addresses of this group's loads
+        // are formed here and not, all eight of them, at the top of the round
+        uint32_t lane_x = na.jv * uint32_t(VEC * sizeof(T));
+        asm volatile("" : "+v"(lane_x));
 #pragma unroll
-      for (int rr = 0; rr < GR; ++rr) fr[r0 + rr] = load_raw<T, VEC>(nxc + (r0 + rr) * m);
+        for (int rr = 0; rr < GR; ++rr) fr[r0 + rr] = load_row<T, VEC>(x, na.g, row_bytes, r0 + rr, lane_x);
+      }
       // keep the instruction scheduler from mixing groups: it would otherwise hoist the table
       // reads of all 8*VEC elements and run out of registers
       __builtin_amdgcn_sched_barrier(0);
     }
-    finish_item<K, VEC>(acc, h32, sx32, payload + ((pos.g * m + pos.jv * VEC) * K), st);
-    pos = npos;
+    finish_item<K, VEC>(acc, h32, sx32, payload + uint64_t(ca.g) * m * uint32_t(K) + ca.jv * uint32_t(VEC * K), ca.counts,
+                        st);
+    cur = nxt;
+    nxt = q.drawn + uint32_t(__builtin_amdgcn_readfirstlane(int(after_v)));
+    ca = na;
   }
-}
-
-// Fused M1..M4.  Items whose eight rows all exist run through a software-pipelined loop:
-// row r of the next item is requested as soon as row r of the current item has been
-// consumed, so a wavefront always has loads in flight while it works; the first item's rows
-// are requested before the tables are built.  The last, partial row group (n % 8 != 0) and
-// the rare case of more than two thresholds per bucket take the plain path.
-template <typename T, int K, int VEC>
-__global__ __launch_bounds__(kBlock, ACCEPT_ENCODE_WAVES) void mbq_encode_kernel(const T* __restrict__ x,
-                                                             const float* __restrict__ alpha_prev,
-                                                             uint8_t* __restrict__ payload,
-                                                             double* __restrict__ partials, int64_t n, int64_t m,
-                                                             int64_t ipg, ItemStep step) {
-  constexpr int NPAIR = K * (K - 1) / 2;
-  constexpr int NSTAT = nstat_of(K);
-  __shared__ EncodeTables<K> tb;
-  __shared__ StatScratch red;
-
-  const int tid = threadIdx.x;
-  const int64_t stride = int64_t(gridDim.x) * kBlock;
-  const int64_t items_full = (n / 8) * ipg;  // items of complete row groups come first
-  int64_t it = int64_t(blockIdx.x) * kBlock + tid;
-  ItemPos pos;
-  pos.g = it / ipg;
-  pos.jv = it - pos.g * ipg;
-
-  // Whole rounds (every thread of the grid has an item) go through the pipelined loop; what is
-  // left of the complete row groups is then spread over the grid one column at a time, so that
-  // no thread carries a whole extra item while the others idle.
-  const int64_t rounds = items_full / stride;
-  RawRow<VEC> fr[8];
-  if (rounds > 0) {
-    const T* xc = x + pos.g * 8 * m + pos.jv * VEC;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) fr[r] = load_raw<T, VEC>(xc + r * m);
-  }
-
-  build_encode_tables<K>(alpha_prev, tb);
-  // the same value in every lane: read it into a scalar register, so that the choice of path
-  // below is a scalar branch and not a divergent one whose sides run one after the other
-  const int maxcnt = __builtin_amdgcn_readfirstlane(tb.maxcnt);
-
-  EncodeStats<K> st;
-  st.Sx = 0.0;
-#pragma unroll
-  for (int p = 0; p < K; ++p) { st.H[p] = 0.0; st.cnt[p] = 0; }
-#pragma unroll
-  for (int i = 0; i < (NPAIR > 0 ? NPAIR : 1); ++i) st.dis[i] = 0;
-
-  const int64_t gtid = int64_t(blockIdx.x) * kBlock + tid;
-  // whole rounds pipelined, then the items of the last, incomplete round one column per thread
-  const int64_t first_left = rounds * stride;
-  const int64_t cols_left = (items_full - first_left) * VEC;
-  if (maxcnt == 1) {
-    encode_rounds<T, K, VEC, 1>(tb, x, payload, m, ipg, rounds, pos, step, fr, st);
-    for (int64_t s = gtid; s < cols_left; s += stride) {
-      const int64_t item = first_left + s / VEC;
-      const int64_t g = item / ipg;
-      encode_column<T, K, 1>(tb, x, payload, n, m, g, (item - g * ipg) * VEC + s % VEC, 1, st);
-    }
-  } else if (maxcnt == 2 && K <= 4) {
-    encode_rounds<T, K, VEC, 2>(tb, x, payload, m, ipg, rounds, pos, step, fr, st);
-    for (int64_t s = gtid; s < cols_left; s += stride) {
-      const int64_t item = first_left + s / VEC;
-      const int64_t g = item / ipg;
-      encode_column<T, K, 2>(tb, x, payload, n, m, g, (item - g * ipg) * VEC + s % VEC, 2, st);
-    }
-  } else {
-    // several thresholds share a bucket (levels closer than a bucket's width): rare.  One column
-    // per thread keeps this path's register needs out of the kernel's budget.
-    const int64_t cols_full = (n / 8) * m;
-    for (int64_t s = gtid; s < cols_full; s += stride) {
-      const int64_t g = s / m;
-      encode_column<T, K, 0>(tb, x, payload, n, m, g, s - g * m, maxcnt, st);
-    }
-  }
-  // the last, partial row group (n % 8 != 0), one column per thread
-  if (n % 8 != 0) {
-    for (int64_t j = gtid; j < m; j += stride)
-      encode_column<T, K, 0>(tb, x, payload, n, m, n / 8, j, maxcnt, st);
-  }
-
-  // M4: workgroup totals in a fixed order -> one record per workgroup, stat-major
-  double sv[NSTAT];
-#pragma unroll
-  for (int p = 0; p < K; ++p) sv[p] = st.H[p];
-  sv[K] = st.Sx;
-#pragma unroll
-  for (int p = 0; p < K; ++p) sv[K + 1 + p] = double(st.cnt[p]);
-#pragma unroll
-  for (int i = 0; i < NPAIR; ++i) sv[2 * K + 1 + i] = double(st.dis[i]);
-  const double total = block_sum_stats<NSTAT>(sv, red);
-  if (tid < NSTAT) partials[int64_t(tid) * gridDim.x + blockIdx.x] = total;
 }
 
 // ========================================================================= finalize (M5)
-// One workgroup: fixed-order float64 totals (one wavefront per statistic), then one thread
-// solves alpha_cur = (B^T B)^-1 B^T x by Gaussian elimination with row pivoting, applies the
-// moving average with beta = min(0.9, (1+t)/(10+t)) and m_q = mean(B alpha_t - x);
-// header = [alpha_t, m_q].  K is a template parameter so that the k x k system lives in
-// registers.
-constexpr int kFinBlock = kBlock;
-constexpr int kFinRPT = (kEncodeGridMax + kFinBlock - 1) / kFinBlock;  // records per thread, at most
+// From the call's totals: alpha_cur = (B^T B)^-1 B^T x by Gaussian elimination with row
+// pivoting, the moving average with beta = min(0.9, (1+t)/(10+t)), m_q = mean(B alpha_t - x);
+// header = [alpha_t, m_q].  One thread; K is a template parameter so that the k x k system
+// lives in registers.  tot: sums of x over the +1 entries of each plane, sum of x, +1 counts
+// per plane, disagreement counts per plane pair.
 template <int K>
-__global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* __restrict__ partials, int nrec,
-                                                               const float* __restrict__ alpha_prev, double n_elems,
-                                                               double t, float* __restrict__ header) {
-  constexpr int NSTAT = nstat_of(K);
-  __shared__ double tot[NSTAT];
-  const int tid = threadIdx.x;
-  // every thread takes records tid, tid+256, ... (at most kFinRPT) of every statistic; the loads
-  // of a statistic are all issued before their adds, so few memory latencies are paid.  Then
-  // the fixed-order workgroup sum: the totals do not depend on timing.
-  __shared__ StatScratch red;
-  double a[NSTAT];
-  double v[NSTAT][kFinRPT];
-#pragma unroll
-  for (int s = 0; s < NSTAT; ++s)
-#pragma unroll
-    for (int i = 0; i < kFinRPT; ++i) {
-      const int b = tid + i * kFinBlock;
-      v[s][i] = (b < nrec) ? partials[int64_t(s) * nrec + b] : 0.0;
-    }
-#pragma unroll
-  for (int s = 0; s < NSTAT; ++s) {
-    a[s] = v[s][0];
-#pragma unroll
-    for (int i = 1; i < kFinRPT; ++i) a[s] += v[s][i];
-  }
-  const double total = block_sum_stats<NSTAT>(a, red);
-  if (tid < NSTAT) tot[tid] = total;
-  __syncthreads();
-  if (tid != 0) return;
+__device__ __forceinline__ void solve_and_write_header(const double* tot, const float* __restrict__ alpha_prev,
+                                                       double n_elems, double t, float* __restrict__ header) {
   double G[K][K], b[K], Sb[K], a_prev[K], cur[K];
   const double Sx = tot[K];
   {
@@ -704,22 +707,167 @@ __global__ __launch_bounds__(kFinBlock) void mbq_finalize_kernel(const double* _
   header[K] = float((dot - Sx) / n_elems);
 }
 
+// What the kernels of one compress call share: the per-workgroup records in the workspace
+// (stat-major: statistic s of workgroup b at records[s * nrec + b]), the previous coefficients
+// and the header to write.
+struct MbqCall {
+  uint32_t* counters;  // work counters of the encode kernel (control block of the workspace)
+  double* records;
+  const float* alpha_prev;
+  float* header;
+  double n_elems, t;
+};
+
+// End of an encode kernel (M4): the workgroup adds up its threads' statistics in a fixed order
+// and stores one record.
+template <int K>
+__device__ __forceinline__ void store_record(const EncodeStats<K>& st, const MbqCall& call, WaveTotals& buf) {
+  constexpr int NPAIR = K * (K - 1) / 2;
+  constexpr int NSTAT = nstat_of(K);
+  double sv[NSTAT];
+#pragma unroll
+  for (int p = 0; p < K; ++p) sv[p] = st.H[p];
+  sv[K] = st.Sx;
+#pragma unroll
+  for (int p = 0; p < K; ++p) sv[K + 1 + p] = double(st.cnt[p]);
+#pragma unroll
+  for (int i = 0; i < NPAIR; ++i) sv[2 * K + 1 + i] = double(st.dis[i]);
+  const double total = block_sum_stats<NSTAT>(sv, buf);
+  if (threadIdx.x < NSTAT) call.records[int64_t(threadIdx.x) * gridDim.x + blockIdx.x] = total;
+}
+
+// M5, one workgroup: thread b takes records b, b + 256, ... of every statistic (all loads of a
+// round issued before their adds), the workgroup adds them up in the same fixed order, one
+// thread solves and writes the header.
+template <int K>
+__global__ __launch_bounds__(kBlock) void mbq_finalize_kernel(MbqCall call, int nrec) {
+  constexpr int NSTAT = nstat_of(K);
+  __shared__ WaveTotals red;
+  __shared__ double tot[48];
+  const int tid = threadIdx.x;
+  double a[NSTAT];
+#pragma unroll
+  for (int s = 0; s < NSTAT; ++s) a[s] = 0.0;
+  for (int b = tid; b < nrec; b += kBlock) {
+    double v[NSTAT];
+#pragma unroll
+    for (int s = 0; s < NSTAT; ++s) v[s] = call.records[int64_t(s) * nrec + b];
+#pragma unroll
+    for (int s = 0; s < NSTAT; ++s) a[s] += v[s];
+  }
+  const double total = block_sum_stats<NSTAT>(a, red);
+  if (tid < NSTAT) tot[tid] = total;
+  if (tid < kMaxGroups) call.counters[tid * kCounterStride] = 0u;  // the encode kernel's work counters, for the next call
+  __syncthreads();
+  if (tid == 0) solve_and_write_header<K>(tot, call.alpha_prev, call.n_elems, call.t, call.header);
+}
+
+// Fused M1..M4.  Complete row groups go through the pipelined stream: row r of the next
+// wave-item is requested as soon as row r of the current one has been consumed, so a wavefront
+// always has loads in flight while it works; the first wave-item's rows are requested before
+// the tables are built.  The last, partial row group (n % 8 != 0) and the rare case of more
+// than two thresholds per bucket take the plain path, one column per thread.
+template <typename T, int K, int VEC>
+__global__ __launch_bounds__(kEncBlock) void mbq_encode_kernel(const T* __restrict__ x, uint8_t* __restrict__ payload,
+                                                               MbqCall call, int64_t n, int64_t m, uint32_t ipg,
+                                                               uint32_t wpg, uint32_t n_wave_items) {
+  constexpr int NPAIR = K * (K - 1) / 2;
+  __shared__ EncodeTables<K> tb;
+  __shared__ WaveTotals red;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  float alpha[K];  // asked for first: nothing below needs them before the tables are built
+#pragma unroll
+  for (int j = 0; j < K; ++j) alpha[j] = call.alpha_prev[j];
+  // this wavefront's place in its group's queue: the first two positions of every wavefront are
+  // fixed (its index among the group's wavefronts, and that plus their number), the rest are drawn
+  WorkQueue q;
+  const uint32_t group = blockIdx.x / uint32_t(kGroupBlocks);
+  const uint32_t groups = (gridDim.x + uint32_t(kGroupBlocks) - 1u) / uint32_t(kGroupBlocks);
+  const uint32_t group_blocks =
+      gridDim.x - group * uint32_t(kGroupBlocks) < uint32_t(kGroupBlocks) ? gridDim.x - group * uint32_t(kGroupBlocks)
+                                                                        : uint32_t(kGroupBlocks);
+  const uint32_t group_waves = group_blocks * uint32_t(kEncWaves);
+  q.counter = call.counters + group * uint32_t(kCounterStride);
+  q.first = group * uint32_t(kGroupSlots);
+  q.sweep = groups * uint32_t(kGroupSlots);
+  {
+    const uint32_t full_sweeps = n_wave_items / q.sweep;
+    const uint32_t rest = n_wave_items - full_sweeps * q.sweep;
+    const uint32_t extra =
+        rest > q.first ? (rest - q.first < uint32_t(kGroupSlots) ? rest - q.first : uint32_t(kGroupSlots)) : 0u;
+    q.count = full_sweeps * uint32_t(kGroupSlots) + extra;
+  }
+  q.drawn = 2u * group_waves;
+  const uint32_t cur = uint32_t(__builtin_amdgcn_readfirstlane(
+      int((blockIdx.x - group * uint32_t(kGroupBlocks)) * uint32_t(kEncWaves) + uint32_t(tid) / uint32_t(kWave))));
+  const uint32_t nxt = cur + group_waves;
+  RawRow<VEC> fr[8];
+  ItemAddr ca;
+  ca.g = 0; ca.jv = 0; ca.counts = false;
+  if (cur < q.count) {
+    ca = item_addr(queue_to_wave_item(cur, q), wpg, ipg, lane);
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+      fr[r] = load_row<T, VEC>(x, ca.g, uint64_t(m) * sizeof(T), r, ca.jv * uint32_t(VEC * sizeof(T)));
+  }
+
+  build_encode_tables<K>(alpha, tb);
+  // the same value in every lane: read it into a scalar register, so that the choice of path
+  // below is a scalar branch and not a divergent one whose sides run one after the other
+  const int maxcnt = __builtin_amdgcn_readfirstlane(tb.maxcnt);
+
+  EncodeStats<K> st;
+  st.Sx = 0.0;
+#pragma unroll
+  for (int p = 0; p < K; ++p) { st.H[p] = 0.0; st.cnt[p] = 0; }
+#pragma unroll
+  for (int i = 0; i < (NPAIR > 0 ? NPAIR : 1); ++i) st.dis[i] = 0;
+
+  const int64_t stride = int64_t(gridDim.x) * kEncBlock;
+  const int64_t gtid = int64_t(blockIdx.x) * kEncBlock + tid;
+  const bool stream = n_wave_items != 0u;  // else: a geometry too narrow for wave-items
+  if (stream && maxcnt == 1) {
+    encode_stream<T, K, VEC, 1>(tb, x, payload, uint64_t(m), ipg, wpg, q, cur, nxt, ca, fr, st);
+  } else if (stream && maxcnt == 2 && K <= 4) {
+    encode_stream<T, K, VEC, 2>(tb, x, payload, uint64_t(m), ipg, wpg, q, cur, nxt, ca, fr, st);
+  } else {
+    // several thresholds share a bucket (levels closer than a bucket's width), or a very narrow
+    // tensor: rare.  One column per thread keeps this path's register needs out of the kernel's
+    // budget.
+    const int64_t cols_full = (n / 8) * m;
+    for (int64_t s = gtid; s < cols_full; s += stride) {
+      const int64_t g = s / m;
+      encode_column<T, K, 0>(tb, x, payload, n, m, g, s - g * m, maxcnt, st);
+    }
+  }
+  // the last, partial row group (n % 8 != 0), one column per thread
+  if (n % 8 != 0) {
+    for (int64_t j = gtid; j < m; j += stride)
+      encode_column<T, K, 0>(tb, x, payload, n, m, n / 8, j, maxcnt, st);
+  }
+  store_record<K>(st, call, red);
+}
+
 // ================================================ comparison layout: one byte per binary base
 // ACCEPT_LAYOUT_UNENCODED: B itself, +1 / -1 as bytes, element-major with the k bases
 // innermost ("w/o enc." in the paper's size table).  Same levels, same sums and the same
 // finalize kernel as the bit-plane path; plain flat loops, four elements per thread and step.
 template <typename T, int K>
 __global__ __launch_bounds__(kBlock) void mbq_encode_plain_kernel(const T* __restrict__ x,
-                                                                  const float* __restrict__ alpha_prev,
-                                                                  uint8_t* __restrict__ payload,
-                                                                  double* __restrict__ partials, int64_t N) {
+                                                                  uint8_t* __restrict__ payload, MbqCall call,
+                                                                  int64_t N) {
   constexpr int NW = (K + 3) / 4;
   constexpr int NPAIR = K * (K - 1) / 2;
-  constexpr int NSTAT = nstat_of(K);
   __shared__ EncodeTables<K> tb;
-  __shared__ StatScratch red;
+  __shared__ WaveTotals red;
+  const float* alpha_prev = call.alpha_prev;
   const int tid = threadIdx.x;
-  build_encode_tables<K>(alpha_prev, tb);
+  float alpha[K];
+#pragma unroll
+  for (int j = 0; j < K; ++j) alpha[j] = alpha_prev[j];
+  build_encode_tables<K>(alpha, tb);
   const int maxcnt = __builtin_amdgcn_readfirstlane(tb.maxcnt);
   EncodeStats<K> st;
   st.Sx = 0.0;
@@ -790,16 +938,7 @@ __global__ __launch_bounds__(kBlock) void mbq_encode_plain_kernel(const T* __res
       for (int p = 0; p < K; ++p) st.H[p] += double(h32[p]);
     }
   }
-  double sv[NSTAT];
-#pragma unroll
-  for (int p = 0; p < K; ++p) sv[p] = st.H[p];
-  sv[K] = st.Sx;
-#pragma unroll
-  for (int p = 0; p < K; ++p) sv[K + 1 + p] = double(st.cnt[p]);
-#pragma unroll
-  for (int i = 0; i < NPAIR; ++i) sv[2 * K + 1 + i] = double(st.dis[i]);
-  const double total = block_sum_stats<NSTAT>(sv, red);
-  if (tid < NSTAT) partials[int64_t(tid) * gridDim.x + blockIdx.x] = total;
+  store_record<K>(st, call, red);
 }
 
 template <typename TO, int K>
@@ -914,44 +1053,182 @@ __global__ __launch_bounds__(kBlock) void mbq_decode_kernel(const uint8_t* __res
   }
 }
 
-// ======================================================= residue initialisation of alpha
-// Pass j: sum of |rho_j| with rho_0 = x, rho_(i+1) = rho_i - alpha_i sign(rho_i), sign(0) = +1,
-// carried in float64; alpha_0..alpha_(j-1) are read from device memory.
+// ======================================================= residue initialisation (batch 0)
+// rho_0 = x, b_j = sign(rho_j) (sign(0) = +1), alpha_j = mean|rho_j|, rho_(j+1) = rho_j - alpha_j b_j,
+// carried in float64 like the definition.  alpha_j needs the whole tensor's |rho_j|, so the method
+// is k passes over x; pass j reads alpha_0..alpha_(j-1) from device memory.
+
+// rho_j of one element.
+__device__ __forceinline__ double residue(float x, const double (&a)[8], int j) {
+  double rho = double(x);
+  for (int q = 0; q < j; ++q) rho -= (rho >= 0.0) ? a[q] : -a[q];
+  return rho;
+}
+
+// Pass j, sums only: sum of |rho_j|, 16-byte streaming loads, four in flight per thread; one
+// record (a single float64) per workgroup.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void mbq_init_pass_kernel(const T* __restrict__ x, int64_t N, int j,
                                                                 const float* __restrict__ alpha,
-                                                                double* __restrict__ partials) {
-  __shared__ double red[kBlock / kWave];
+                                                                double* __restrict__ records) {
+  constexpr int VEC = Elem<T>::VEC;
+  constexpr int UNROLL = 4;
+  __shared__ WaveTotals red;
   double a[8];
-  for (int i = 0; i < j; ++i) a[i] = double(alpha[i]);
+  for (int i = 0; i < 8; ++i) a[i] = i < j ? double(alpha[i]) : 0.0;
+  const int64_t nvec = N / VEC;
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
   double acc = 0.0;
-  for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < N; i += int64_t(gridDim.x) * kBlock) {
-    double rho = double(load_one(x + i));
-    for (int q = 0; q < j; ++q) rho -= (rho >= 0.0) ? a[q] : -a[q];
-    acc += fabs(rho);
+  int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  for (; v + (UNROLL - 1) * stride < nvec; v += UNROLL * stride) {
+    float f[UNROLL][VEC];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) load_vec_stream(x + (v + u * stride) * VEC, f[u]);
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc += fabs(residue(f[u][e], a, j));
   }
-  acc = wave_sum(acc);
-  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double t = red[0];
-    for (int w = 1; w < kBlock / kWave; ++w) t += red[w];
-    partials[blockIdx.x] = t;
+  for (; v < nvec; v += stride) {
+    float f[VEC];
+    load_vec_stream(x + v * VEC, f);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc += fabs(residue(f[e], a, j));
   }
+  if (blockIdx.x == 0 && int64_t(threadIdx.x) < N - nvec * VEC)
+    acc += fabs(residue(load_one(x + nvec * VEC + threadIdx.x), a, j));
+  const double sv[1] = {acc};
+  const double total = block_sum_stats<1>(sv, red);
+  if (threadIdx.x == 0) records[blockIdx.x] = total;
 }
-__global__ __launch_bounds__(kBlock) void mbq_init_finalize_kernel(const double* __restrict__ partials, int nrec,
-                                                                    double n_elems, int j, float* __restrict__ alpha) {
-  __shared__ double red[kBlock];
-  const int tid = threadIdx.x;
-  double a = 0.0;
-  for (int b = tid; b < nrec; b += kBlock) a += partials[b];
-  red[tid] = a;
-  __syncthreads();
-  for (int off = kBlock / 2; off > 0; off >>= 1) {
-    if (tid < off) red[tid] += red[tid + off];
-    __syncthreads();
+
+// Last pass (j = K-1) of a batch-0 compression: the signs b_0..b_(K-1) of every element need
+// only alpha_0..alpha_(K-2), so the bit planes of B^0 are written in the same pass that adds up
+// |rho_(K-1)| for alpha_(K-1).  Items as in the encoder (8 rows x VEC columns per lane, row loads
+// contiguous across lanes), static grid-stride assignment.  Record per workgroup: sum|rho_(K-1)|,
+// sum of x, +1 counts of the K planes.
+template <typename T, int K, int VEC>
+__global__ __launch_bounds__(kBlock) void mbq_init_encode_kernel(const T* __restrict__ x,
+                                                                  const float* __restrict__ alpha,
+                                                                  uint8_t* __restrict__ payload,
+                                                                  double* __restrict__ records, int64_t n, int64_t m,
+                                                                  int64_t ipg, int64_t items, ItemStep step) {
+  constexpr int NW = (K + 3) / 4;
+  constexpr int NDW = (VEC * K + 3) / 4;
+  constexpr int NS = K + 2;
+  __shared__ WaveTotals red;
+  double a[8];
+  for (int i = 0; i < 8; ++i) a[i] = i < K - 1 ? double(alpha[i]) : 0.0;
+  double sum_abs = 0.0, sum_x = 0.0;
+  uint32_t cnt[K];
+#pragma unroll
+  for (int p = 0; p < K; ++p) cnt[p] = 0;
+  int64_t it = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+  ItemPos pos;
+  pos.g = it / ipg;
+  pos.jv = it - pos.g * ipg;
+  for (; it < items; it += int64_t(gridDim.x) * kBlock, item_advance(pos, step, ipg)) {
+    const int64_t row0 = pos.g * 8;
+    const int nrows = (n - row0) < 8 ? int(n - row0) : 8;
+    const T* xc = x + row0 * m + pos.jv * VEC;
+    RawRow<VEC> fr[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {  // all row loads first, so that they overlap
+      if constexpr (VEC > 1) fr[r].v = make_uint4(0u, 0u, 0u, 0u); else fr[r].v = 0u;
+      if (r < nrows) fr[r] = load_raw<T, VEC>(xc + r * m);
+    }
+    uint32_t acc[VEC][NW];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c)
+#pragma unroll
+      for (int w = 0; w < NW; ++w) acc[c][w] = 0;
+    float sx32 = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      float row[VEC];
+      widen_raw<VEC>(fr[r], row);
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) {
+        // the recurrence of residue(), keeping every sign on the way
+        double rho = double(row[c]);
+        uint32_t sp[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sp[w] = 0;
+#pragma unroll
+        for (int q = 0; q < K; ++q) {
+          const bool pos_sign = rho >= 0.0;
+          sp[q / 4] |= (pos_sign ? 1u : 0u) << (8 * (q % 4));
+          if (q < K - 1) rho -= pos_sign ? a[q] : -a[q];
+        }
+        const bool have = r < nrows;  // a missing row contributes 0 bits and nothing to the sums
+        sum_abs += have ? fabs(rho) : 0.0;
+        sx32 = __fadd_rn(sx32, have ? row[c] : 0.0f);
+#pragma unroll
+        for (int w = 0; w < NW; ++w) acc[c][w] = (acc[c][w] << 1) | (have ? sp[w] : 0u);
+      }
+    }
+    sum_x += double(sx32);
+#pragma unroll
+    for (int p = 0; p < K; ++p)
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) cnt[p] += __popc((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu);
+    uint8_t* dst = payload + ((pos.g * m + pos.jv * VEC) * K);
+    if constexpr (VEC > 1) {
+      uint32_t out[NDW];
+#pragma unroll
+      for (int w = 0; w < NDW; ++w) out[w] = 0;
+#pragma unroll
+      for (int c = 0; c < VEC; ++c)
+#pragma unroll
+        for (int p = 0; p < K; ++p) {
+          const int b = c * K + p;
+          out[b / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (b % 4));
+        }
+      store_dwords<NDW>(reinterpret_cast<uint32_t*>(dst), out);
+    } else {
+#pragma unroll
+      for (int p = 0; p < K; ++p) dst[p] = uint8_t(acc[0][p / 4] >> (8 * (p % 4)));
+    }
   }
-  if (tid == 0) alpha[j] = float(red[0] / n_elems);
+  double sv[NS];
+  sv[0] = sum_abs;
+  sv[1] = sum_x;
+#pragma unroll
+  for (int p = 0; p < K; ++p) sv[2 + p] = double(cnt[p]);
+  const double total = block_sum_stats<NS>(sv, red);
+  if (threadIdx.x < NS) records[int64_t(threadIdx.x) * gridDim.x + blockIdx.x] = total;
+}
+
+// After pass j: alpha_j = (sum of the workgroups' |rho_j| sums) / N, written to alpha_out[j].
+// After the last pass of a batch-0 compression (nstat = k + 2) also the rest of the header:
+// m_q = mean(B^0 alpha^0 - x) = (sum_p alpha_p (2 cnt_p - N) - sum x) / N  (eq. (biased error)),
+// written behind the k coefficients that the earlier passes left in alpha_out.
+__global__ __launch_bounds__(kBlock) void mbq_init_finalize_kernel(const double* __restrict__ records, int nrec,
+                                                                    int nstat, double n_elems, int j,
+                                                                    float* __restrict__ alpha_out) {
+  __shared__ WaveTotals red;
+  __shared__ double tot[16];
+  const int tid = threadIdx.x;
+  for (int s = 0; s < nstat; ++s) {
+    double a = 0.0;
+    for (int b = tid; b < nrec; b += kBlock) a += records[int64_t(s) * nrec + b];
+    const double sv[1] = {a};
+    const double total = block_sum_stats<1>(sv, red);
+    if (tid == 0) tot[s] = total;
+    __syncthreads();  // the buffer of the workgroup sum is free again
+  }
+  if (tid != 0) return;
+  const float a_j = float(tot[0] / n_elems);
+  alpha_out[j] = a_j;
+  if (nstat > 1) {
+    const int k = nstat - 2;
+    double dot = 0.0;
+    for (int p = 0; p < k; ++p) {
+      const double a_p = p == j ? double(a_j) : double(alpha_out[p]);
+      dot += a_p * (2.0 * tot[2 + p] - n_elems);
+    }
+    alpha_out[k] = float((dot - tot[1]) / n_elems);
+  }
 }
 
 // ============================================================================= host side
@@ -974,27 +1251,37 @@ ItemStep step_for(int grid, int64_t ipg) {
   return st;
 }
 
+MbqCall make_call(const accept_desc& d, const float* alpha_prev, void* header, void* ws) {
+  MbqCall c;
+  c.counters = static_cast<uint32_t*>(ws);
+  c.records = reinterpret_cast<double*>(static_cast<char*>(ws) + kCtrlBytes);
+  c.alpha_prev = alpha_prev;
+  c.header = static_cast<float*>(header);
+  c.n_elems = double(d.n) * double(d.m);
+  c.t = double(d.t);
+  return c;
+}
+
 template <typename T, int K, int VEC>
-hipError_t launch_encode(const accept_desc& d, const MPlan& p, const T* x, const float* alpha_prev, uint8_t* payload,
-                         double* partials, hipStream_t s) {
-  const int64_t ipg = d.m / VEC;
-  hipLaunchKernelGGL((mbq_encode_kernel<T, K, VEC>), dim3(p.grid), dim3(kBlock), 0, s, x, alpha_prev, payload,
-                     partials, d.n, d.m, ipg, step_for(p.grid, ipg));
+hipError_t launch_encode(const accept_desc& d, const MPlan& p, const T* x, uint8_t* payload, const MbqCall& call,
+                         hipStream_t s) {
+  hipLaunchKernelGGL((mbq_encode_kernel<T, K, VEC>), dim3(p.grid), dim3(kEncBlock), 0, s, x, payload, call, d.n, d.m,
+                     uint32_t(p.stream ? d.m / VEC : 1), p.wpg, p.n_wave_items);
   return hipGetLastError();
 }
 
 template <typename T, int VEC>
-hipError_t encode_k(const accept_desc& d, const MPlan& p, const T* x, const float* alpha_prev, uint8_t* payload,
-                    double* partials, hipStream_t s) {
+hipError_t encode_k(const accept_desc& d, const MPlan& p, const T* x, uint8_t* payload, const MbqCall& call,
+                    hipStream_t s) {
   switch (d.bits) {
-    case 1: return launch_encode<T, 1, VEC>(d, p, x, alpha_prev, payload, partials, s);
-    case 2: return launch_encode<T, 2, VEC>(d, p, x, alpha_prev, payload, partials, s);
-    case 3: return launch_encode<T, 3, VEC>(d, p, x, alpha_prev, payload, partials, s);
-    case 4: return launch_encode<T, 4, VEC>(d, p, x, alpha_prev, payload, partials, s);
-    case 5: return launch_encode<T, 5, VEC>(d, p, x, alpha_prev, payload, partials, s);
-    case 6: return launch_encode<T, 6, VEC>(d, p, x, alpha_prev, payload, partials, s);
-    case 7: return launch_encode<T, 7, VEC>(d, p, x, alpha_prev, payload, partials, s);
-    case 8: return launch_encode<T, 8, VEC>(d, p, x, alpha_prev, payload, partials, s);
+    case 1: return launch_encode<T, 1, VEC>(d, p, x, payload, call, s);
+    case 2: return launch_encode<T, 2, VEC>(d, p, x, payload, call, s);
+    case 3: return launch_encode<T, 3, VEC>(d, p, x, payload, call, s);
+    case 4: return launch_encode<T, 4, VEC>(d, p, x, payload, call, s);
+    case 5: return launch_encode<T, 5, VEC>(d, p, x, payload, call, s);
+    case 6: return launch_encode<T, 6, VEC>(d, p, x, payload, call, s);
+    case 7: return launch_encode<T, 7, VEC>(d, p, x, payload, call, s);
+    case 8: return launch_encode<T, 8, VEC>(d, p, x, payload, call, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -1024,6 +1311,32 @@ hipError_t decode_k(const accept_desc& d, const uint8_t* payload, const float* h
   }
 }
 
+template <typename T, int K, int VEC>
+hipError_t launch_init_encode(const accept_desc& d, const T* x, const float* alpha, uint8_t* payload, double* records,
+                              int grid, hipStream_t s) {
+  const int64_t ipg = d.m / VEC;
+  const int64_t items = ((d.n + 7) / 8) * ipg;
+  hipLaunchKernelGGL((mbq_init_encode_kernel<T, K, VEC>), dim3(grid), dim3(kBlock), 0, s, x, alpha, payload, records,
+                     d.n, d.m, ipg, items, step_for(grid, ipg));
+  return hipGetLastError();
+}
+
+template <typename T, int VEC>
+hipError_t init_encode_k(const accept_desc& d, const T* x, const float* alpha, uint8_t* payload, double* records,
+                         int grid, hipStream_t s) {
+  switch (d.bits) {
+    case 1: return launch_init_encode<T, 1, VEC>(d, x, alpha, payload, records, grid, s);
+    case 2: return launch_init_encode<T, 2, VEC>(d, x, alpha, payload, records, grid, s);
+    case 3: return launch_init_encode<T, 3, VEC>(d, x, alpha, payload, records, grid, s);
+    case 4: return launch_init_encode<T, 4, VEC>(d, x, alpha, payload, records, grid, s);
+    case 5: return launch_init_encode<T, 5, VEC>(d, x, alpha, payload, records, grid, s);
+    case 6: return launch_init_encode<T, 6, VEC>(d, x, alpha, payload, records, grid, s);
+    case 7: return launch_init_encode<T, 7, VEC>(d, x, alpha, payload, records, grid, s);
+    case 8: return launch_init_encode<T, 8, VEC>(d, x, alpha, payload, records, grid, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 }  // namespace
 
 MPlan make_mplan(const accept_desc& d) {
@@ -1031,35 +1344,39 @@ MPlan make_mplan(const accept_desc& d) {
   p.vec = vec_for(d.in_dtype, d.m);
   p.G = (d.n + 7) / 8;
   p.items = p.G * (d.m / p.vec);
-  // Grid of the encode kernel.  Its fast loop runs whole rounds (every thread of the grid has an
-  // item) and what is left over goes one column per thread, so a tensor with fewer items than
-  // the largest grid has threads gets the largest grid that still fills one round (rounding the
-  // grid up instead would leave every item to the slower leftover path).  The columns of a last,
-  // partial row group also go one per thread: the grid is at least wide enough for them.
+  // The pipelined stream of the encode kernel works on wave-items (64 items of one row group).
+  // It needs at least one full wave-item per row group to be worth it and 32-bit wave-item
+  // numbers; other geometries (very narrow tensors) go one column per thread.
+  const int64_t ipg = d.m / p.vec;
+  const int64_t wpg = (ipg + kWave - 1) / kWave;
+  const int64_t full_groups = d.n / 8;
+  const int64_t wave_items = full_groups * wpg;
+  p.stream = full_groups > 0 && ipg >= kWave && wave_items < (int64_t(1) << 31) && d.m * 8 < (int64_t(1) << 32);
+  p.wpg = p.stream ? uint32_t(wpg) : 1u;
+  p.n_wave_items = p.stream ? uint32_t(wave_items) : 0u;
   {
-    const int64_t items_full = (d.n / 8) * (d.m / p.vec);
-    int64_t blocks = items_full / kBlock;
-    const int64_t tail_blocks = (d.n % 8 != 0) ? (d.m + kBlock - 1) / kBlock : 0;
+    // one workgroup of 12 wavefronts per compute unit at most; fewer when there is less work
+    int64_t blocks = p.stream ? (wave_items + kEncWaves - 1) / kEncWaves
+                              : (full_groups * d.m + kEncBlock - 1) / kEncBlock;
+    const int64_t tail_blocks = (d.n % 8 != 0) ? (d.m + kEncBlock - 1) / kEncBlock : 0;
     if (blocks < tail_blocks) blocks = tail_blocks;
     if (blocks < 1) blocks = 1;
     p.grid = int(blocks < kEncodeGridMax ? blocks : kEncodeGridMax);
   }
   p.nstat = nstat_of(d.bits);
-  // records of the encode kernel (stat-major, kEncodeGridMax wide at most) and, for the
-  // residue initialisation, kInitGrid partial sums: both fit the same area
-  size_t bytes = size_t(nstat_of(8)) * 2048 * sizeof(double);
+  // control block, then room for kMaxRecords records of the widest kind (k = 8)
+  const size_t bytes = kCtrlBytes + size_t(nstat_of(8)) * kMaxRecords * sizeof(double);
   p.bytes = (bytes + 255) / 256 * 256;
   return p;
 }
 
 template <typename T>
-hipError_t encode_plain_k(const accept_desc& d, int grid, const T* x, const float* alpha_prev, uint8_t* payload,
-                          double* partials, hipStream_t s) {
+hipError_t encode_plain_k(const accept_desc& d, int grid, const T* x, uint8_t* payload, const MbqCall& call,
+                          hipStream_t s) {
   const int64_t N = d.n * d.m;
-#define ACCEPT_ENC(KK)                                                                                          \
-  case KK:                                                                                                      \
-    hipLaunchKernelGGL((mbq_encode_plain_kernel<T, KK>), dim3(grid), dim3(kBlock), 0, s, x, alpha_prev, payload, \
-                       partials, N);                                                                            \
+#define ACCEPT_ENC(KK)                                                                                         \
+  case KK:                                                                                                     \
+    hipLaunchKernelGGL((mbq_encode_plain_kernel<T, KK>), dim3(grid), dim3(kBlock), 0, s, x, payload, call, N); \
     break;
   switch (d.bits) {
     ACCEPT_ENC(1) ACCEPT_ENC(2) ACCEPT_ENC(3) ACCEPT_ENC(4) ACCEPT_ENC(5) ACCEPT_ENC(6) ACCEPT_ENC(7) ACCEPT_ENC(8)
@@ -1089,33 +1406,27 @@ hipError_t decode_plain_k(const accept_desc& d, const uint8_t* payload, const fl
 
 hipError_t launch_mbq_compress(const accept_desc& d, const MPlan& p, const void* x, const float* alpha_prev,
                                void* header, void* payload, void* ws, hipStream_t s, StageTimer* tm) {
-  double* partials = static_cast<double*>(ws);
+  const MbqCall call = make_call(d, alpha_prev, header, ws);
   uint8_t* pl = static_cast<uint8_t*>(payload);
   hipError_t e;
   mark(tm, s);
   int nrec = p.grid;
   if (d.layout == ACCEPT_LAYOUT_UNENCODED) {
-    nrec = grid_for(d.n * d.m / 4 + 4, kEncodeGridMax);
-    e = d.in_dtype == ACCEPT_BF16
-            ? encode_plain_k<bf16_t>(d, nrec, static_cast<const bf16_t*>(x), alpha_prev, pl, partials, s)
-            : encode_plain_k<float>(d, nrec, static_cast<const float*>(x), alpha_prev, pl, partials, s);
+    const int grid = nrec = grid_for(d.n * d.m / 4 + 4, kPlainGridMax);
+    e = d.in_dtype == ACCEPT_BF16 ? encode_plain_k<bf16_t>(d, grid, static_cast<const bf16_t*>(x), pl, call, s)
+                                  : encode_plain_k<float>(d, grid, static_cast<const float*>(x), pl, call, s);
   } else if (d.in_dtype == ACCEPT_BF16) {
     const bf16_t* xb = static_cast<const bf16_t*>(x);
-    e = p.vec == 8 ? encode_k<bf16_t, 8>(d, p, xb, alpha_prev, pl, partials, s)
-                   : encode_k<bf16_t, 1>(d, p, xb, alpha_prev, pl, partials, s);
+    e = p.vec == 8 ? encode_k<bf16_t, 8>(d, p, xb, pl, call, s) : encode_k<bf16_t, 1>(d, p, xb, pl, call, s);
   } else {
     const float* xf = static_cast<const float*>(x);
-    e = p.vec == 4 ? encode_k<float, 4>(d, p, xf, alpha_prev, pl, partials, s)
-                   : encode_k<float, 1>(d, p, xf, alpha_prev, pl, partials, s);
+    e = p.vec == 4 ? encode_k<float, 4>(d, p, xf, pl, call, s) : encode_k<float, 1>(d, p, xf, pl, call, s);
   }
   if (e != hipSuccess) return e;
   mark(tm, s);
-  const double n_elems = double(d.n) * double(d.m);
-  float* hdr = static_cast<float*>(header);
-#define ACCEPT_FIN(KK)                                                                                         \
-  case KK:                                                                                                     \
-    hipLaunchKernelGGL(mbq_finalize_kernel<KK>, dim3(1), dim3(kFinBlock), 0, s, partials, nrec, alpha_prev,   \
-                       n_elems, double(d.t), hdr);                                                             \
+#define ACCEPT_FIN(KK)                                                                          \
+  case KK:                                                                                      \
+    hipLaunchKernelGGL(mbq_finalize_kernel<KK>, dim3(1), dim3(kBlock), 0, s, call, nrec);       \
     break;
   switch (d.bits) {
     ACCEPT_FIN(1) ACCEPT_FIN(2) ACCEPT_FIN(3) ACCEPT_FIN(4) ACCEPT_FIN(5) ACCEPT_FIN(6) ACCEPT_FIN(7) ACCEPT_FIN(8)
@@ -1150,22 +1461,45 @@ hipError_t launch_mbq_decompress(const accept_desc& d, const void* header, const
   return hipSuccess;
 }
 
-hipError_t launch_mbq_init(const accept_desc& d, const MPlan& p, const void* x, float* alpha0, void* ws,
-                           hipStream_t s) {
-  (void)p;
-  double* partials = static_cast<double*>(ws);
+// Residue initialisation.  payload == nullptr: k sum passes, alpha^0 to alpha_out[0..k).
+// Otherwise a batch-0 compression: k - 1 sum passes and one pass that also writes the bit planes
+// of B^0 to payload; alpha_out is then the header, [alpha^0, m_q].
+hipError_t launch_mbq_init(const accept_desc& d, const MPlan& p, const void* x, float* alpha_out, void* payload,
+                           void* ws, hipStream_t s) {
+  double* records = reinterpret_cast<double*>(static_cast<char*>(ws) + kCtrlBytes);
   const int64_t N = d.n * d.m;
-  const int grid = grid_for(N, kInitGrid);
-  for (int j = 0; j < d.bits; ++j) {
-    if (d.in_dtype == ACCEPT_BF16)
-      hipLaunchKernelGGL((mbq_init_pass_kernel<bf16_t>), dim3(grid), dim3(kBlock), 0, s,
-                         static_cast<const bf16_t*>(x), N, j, alpha0, partials);
-    else
-      hipLaunchKernelGGL((mbq_init_pass_kernel<float>), dim3(grid), dim3(kBlock), 0, s, static_cast<const float*>(x),
-                         N, j, alpha0, partials);
-    hipError_t e = hipGetLastError();
+  const int k = d.bits;
+  const bool bf = d.in_dtype == ACCEPT_BF16;
+  const int grid = grid_for(N / (bf ? 8 : 4) / 4 + 1, kInitGrid);
+  hipError_t e;
+  for (int j = 0; j < k; ++j) {
+    const bool planes = payload != nullptr && j == k - 1;
+    int nrec = grid, nstat = 1;
+    if (planes) {
+      nrec = grid_for(p.items, kPlainGridMax);
+      nstat = k + 2;
+      uint8_t* pl = static_cast<uint8_t*>(payload);
+      if (bf) {
+        const bf16_t* xb = static_cast<const bf16_t*>(x);
+        e = p.vec == 8 ? init_encode_k<bf16_t, 8>(d, xb, alpha_out, pl, records, nrec, s)
+                       : init_encode_k<bf16_t, 1>(d, xb, alpha_out, pl, records, nrec, s);
+      } else {
+        const float* xf = static_cast<const float*>(x);
+        e = p.vec == 4 ? init_encode_k<float, 4>(d, xf, alpha_out, pl, records, nrec, s)
+                       : init_encode_k<float, 1>(d, xf, alpha_out, pl, records, nrec, s);
+      }
+    } else {
+      if (bf)
+        hipLaunchKernelGGL((mbq_init_pass_kernel<bf16_t>), dim3(grid), dim3(kBlock), 0, s,
+                           static_cast<const bf16_t*>(x), N, j, alpha_out, records);
+      else
+        hipLaunchKernelGGL((mbq_init_pass_kernel<float>), dim3(grid), dim3(kBlock), 0, s, static_cast<const float*>(x),
+                           N, j, alpha_out, records);
+      e = hipGetLastError();
+    }
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(mbq_init_finalize_kernel, dim3(1), dim3(kBlock), 0, s, partials, grid, double(N), j, alpha0);
+    hipLaunchKernelGGL(mbq_init_finalize_kernel, dim3(1), dim3(kBlock), 0, s, records, nrec, nstat, double(N), j,
+                       alpha_out);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

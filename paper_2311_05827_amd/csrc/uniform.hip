@@ -735,7 +735,7 @@ hipError_t launch_quant_k(const accept_desc& d, const UPlan& p, const T* x, floa
 template <typename T>
 hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, float* header, uint32_t* payload,
                           void* ws, hipStream_t s, StageTimer* tm) {
-  float* partials = reinterpret_cast<float*>(ws);
+  float* partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + kCtrlBytes);
   float* rtab = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + p.off_rtab);
   mark(tm, s);
   if (p.mode == U_TENSOR) {
@@ -911,7 +911,7 @@ UPlan make_uplan(const accept_desc& d) {
     p.fast = (p.seg_len % p.vec == 0);
     partial_bytes = size_t(p.C) * sizeof(uint32_t);
   }
-  p.off_rtab = (partial_bytes + 255) / 256 * 256;
+  p.off_rtab = kCtrlBytes + (partial_bytes + 255) / 256 * 256;
   p.bytes = p.off_rtab + (size_t(p.C) * sizeof(float) + 255) / 256 * 256;
   return p;
 }

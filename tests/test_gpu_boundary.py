@@ -38,17 +38,14 @@ def test_forward_chain_with_width_changes(mods):
         t = fwd.t
         d, header, payload = fwd.compress(xd)
         torch.cuda.synchronize()
-        if fresh:
-            exp0, _ = orc.mbq_residue_init(x, k)
-            alpha_prev = exp0  # the GPU's initial alpha agrees with the oracle's to 1e-6: checked below
-            # take the GPU's own alpha0 bits for the exact payload comparison
-            d0 = A.make_desc(A.MBQ, k, n, m)
-            a0 = A.accept_mbq_init(d0, xd).cpu().numpy()
-            assert np.all(np.abs(a0 - exp0) <= 1e-6 * np.abs(exp0).sum())
-            alpha_prev = a0
-        oh, op = orc.mbq_compress(x, k, n, m, alpha_prev, t)
-        assert first_mismatch(dev_bytes(payload), op.tobytes()) is None
         gh = np.frombuffer(dev_bytes(header), dtype="<f4")
+        if fresh:
+            # batch 0 (and the first batch after a width change): the residue method's own B^0, alpha^0
+            oh, _ = orc.mbq_compress_first(x, k, n, m)
+            op = orc.mbq_pack(orc.mbq_residue_signs(x, gh[:k]), k, n, m)  # B^0 for the GPU's alpha^0 bits
+        else:
+            oh, op = orc.mbq_compress(x, k, n, m, alpha_prev, t)
+        assert first_mismatch(dev_bytes(payload), op.tobytes()) is None
         ohf = np.frombuffer(oh, dtype="<f4")
         assert np.all(np.abs(gh - ohf) <= 1e-6 * np.abs(ohf[:k]).sum())
         assert fwd.alpha.cpu().numpy().tobytes() == gh[:k].tobytes()
@@ -83,10 +80,9 @@ def test_straight_through_estimator(mods, compressed_backward):
     y = Bd.boundary(x, fwd, bwd)
     (y * w).sum().backward()
     torch.cuda.synchronize()
-    # forward value: the oracle's decompress(compress(x)) from the GPU's alpha0
+    # forward value: batch 0, i.e. the oracle's decompress(compress_first(x))
     k = 2
-    a0 = A.accept_mbq_init(A.make_desc(A.MBQ, k, n, m), x.detach().view(-1)).cpu().numpy()
-    oh, op = orc.mbq_compress(x_np, k, n, m, a0, 0)
+    oh, op = orc.mbq_compress_first(x_np, k, n, m)
     ref = orc.mbq_decompress(oh, op, k, n, m).reshape(n, m)
     scale = float(np.abs(np.frombuffer(oh, dtype="<f4")[:k]).sum())
     assert np.all(np.abs(y.detach().cpu().numpy() - ref) <= 1e-6 * scale)

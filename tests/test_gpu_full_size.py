@@ -93,6 +93,16 @@ def check_mbq_full(A, name, k, t=1, view=None):
     assert verr <= 1e-6 * scale
     # bias correction: the output keeps the input's mean
     assert abs(float(got.astype(np.float64).mean()) - float(x.astype(np.float64).mean())) <= 2e-6 * scale
+    # batch 0 of an epoch on the same tensor: B^0 bit-exact for the GPU's alpha^0, header within tolerance
+    h0, p0 = A.accept_mbq_compress_first(d, xd)
+    torch.cuda.synchronize()
+    g0 = np.frombuffer(dev_bytes(h0), dtype="<f4")
+    assert g0[:k].tobytes() == alpha.tobytes()
+    o0, _ = orc.mbq_compress_first(x, k, n, m)
+    o0f = np.frombuffer(o0, dtype="<f4")
+    assert np.all(np.abs(g0.astype(np.float64) - o0f.astype(np.float64)) <= 1e-6 * np.abs(o0f[:k]).sum()), (g0, o0f)
+    mm = first_mismatch(dev_bytes(p0), orc.mbq_pack(orc.mbq_residue_signs(x, g0[:k]), k, n, m).tobytes())
+    assert mm is None, mm
 
 
 # ---- config 1: 4x64x32x32 post-ReLU activation, 8-bit round trip (and the forward widths)

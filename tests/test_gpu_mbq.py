@@ -161,3 +161,37 @@ def test_residue_init(A, k):
         exp, _ = orc.mbq_residue_init(xin, k)
         got = a0.cpu().numpy()
         assert np.all(np.abs(got.astype(np.float64) - exp.astype(np.float64)) <= 1e-6 * float(np.sum(np.abs(exp)))), (got, exp)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 6])
+def test_batch0_compress(A, k):
+    """accept_mbq_compress_first: header [alpha^0, m_q] within 1e-6 * sum|alpha| of the oracle's,
+    bit planes of B^0 bit-exact for the GPU's own alpha^0 bits, and the decoder reads the pair
+    like any other batch."""
+    torch = torch_mod()
+    for shape, bf in [((16, 1000), False), ((7, 333), False), ((21, 4100), False), ((24, 2056), True), ((10, 1004), True),
+                      ((64, 8192 + 4), False)]:
+        n, m = shape
+        print("batch0 k", k, "shape", shape, "bf16", bf, flush=True)
+        x = si.make_shape("relu_lognormal", shape, 6500 + k)
+        x.reshape(-1)[::97] = 0.0
+        xd, bits = to_dev(x, bf)
+        xin = orc.widen_bf16(bits) if bf else x
+        d = A.make_desc(A.MBQ, k, n, m, in_dtype=A.BF16 if bf else A.F32)
+        header, payload = A.accept_mbq_compress_first(d, xd)
+        xh = A.accept_decompress(d, header, payload)
+        torch.cuda.synchronize()
+        gh = np.frombuffer(dev_bytes(header), dtype="<f4")
+        oh, _ = orc.mbq_compress_first(xin, k, n, m)
+        ohf = np.frombuffer(oh, dtype="<f4")
+        scale = float(np.sum(np.abs(ohf[:k])))
+        assert np.all(np.abs(gh.astype(np.float64) - ohf.astype(np.float64)) <= 1e-6 * scale), (gh, ohf)
+        op = orc.mbq_pack(orc.mbq_residue_signs(xin, gh[:k]), k, n, m)
+        mm = first_mismatch(dev_bytes(payload), op.tobytes())
+        assert mm is None, "B^0 planes differ: " + mm
+        ref = orc.mbq_decompress(dev_bytes(header), op, k, n, m)
+        assert out_to_numpy(xh).tobytes() == ref.tobytes()
+        # the stand-alone initialisation gives the same alpha^0 bits
+        a0 = A.accept_mbq_init(d, xd)
+        torch.cuda.synchronize()
+        assert a0.cpu().numpy().tobytes() == gh[:k].tobytes()

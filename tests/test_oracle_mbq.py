@@ -189,3 +189,39 @@ def test_bf16_input_equals_widened_input():
     h1, p1 = orc.mbq_compress(bits, 3, 8, 64, a0, 2, in_bf16=True)
     h2, p2 = orc.mbq_compress(orc.widen_bf16(bits), 3, 8, 64, a0, 2)
     assert h1 == h2 and p1.tobytes() == p2.tobytes()
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_batch0_compress_pins(k):
+    """Batch 0 ("Forward Quantizer": B^0, alpha^0 from the residue method are what is sent).
+    Pins: a Python-float brute force of the residue recurrence on a tiny tensor; the decoded
+    tensor keeps the input's mean (the header's m_q is the mean error of B^0 alpha^0); every
+    decoded value is the chosen level minus m_q; for k = 1 the decoded magnitudes are mean|x|."""
+    rng = np.random.default_rng(300 + k)
+    n, m = 11, 37
+    x = (rng.standard_normal((n, m)) * 0.7).astype(np.float32)
+    x[0, :5] = 0.0  # sign(0) = +1
+    hdr, pay = orc.mbq_compress_first(x, k, n, m)
+    h = np.frombuffer(hdr, dtype="<f4")
+    alpha = h[:k]
+    # brute force, element by element, in Python floats (float64)
+    codes = []
+    for v in x.reshape(-1).tolist():
+        rho, c = float(v), 0
+        for j in range(k):
+            s = 1.0 if rho >= 0.0 else -1.0
+            c |= (1 if s > 0 else 0) << j
+            rho -= s * float(alpha[j])
+        codes.append(c)
+    assert orc.mbq_unpack(pay, k, n, m).tolist() == codes
+    assert orc.mbq_residue_signs(x, alpha).tolist() == codes
+    assert pay.size == ((n + 7) // 8) * m * k and len(hdr) == 4 * (k + 1)
+    xh = orc.mbq_decompress(hdr, pay, k, n, m)
+    assert abs(float(xh.astype(np.float64).mean()) - float(x.astype(np.float64).mean())) <= 2e-7 * float(np.abs(alpha).sum())
+    lv = [sum((1.0 if (c >> j) & 1 else -1.0) * float(alpha[j]) for j in range(k)) for c in codes]
+    assert np.allclose(xh, np.array(lv) - float(h[k]), rtol=0, atol=1e-6)
+    if k == 1:
+        assert alpha[0] == np.float32(np.mean(np.abs(x.astype(np.float64))))
+    # the same alpha^0 as the stand-alone initialisation, and a usable alpha_prev for batch 1
+    a0, _ = orc.mbq_residue_init(x, k)
+    assert a0.tobytes() == alpha.tobytes()
