@@ -41,23 +41,21 @@ def hipcc_path():
     raise RuntimeError("hipcc not found (looked at $HIPCC, /opt/rocm/bin/hipcc, PATH)")
 
 
-def _compile(hipcc, src, obj, extra):
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(hipcc, src, obj):
+    cmd = [hipcc] + HIPCC_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     return src, r.returncode, (r.stdout + r.stderr), " ".join(cmd)
 
 
-def build(verbose=True, extra_flags=(), lib_path=LIB_PATH, build_dir=None):
-    """Compile every HIP source and link libaccept.so.  Always recompiles.
-
-    extra_flags (e.g. ``-DACCEPT_RANGE_GRID=512``) and lib_path exist for tuning sweeps that
-    build variants side by side; the product is the default call."""
+def build(verbose=True):
+    """Compile every HIP source and link libaccept.so.  Always recompiles."""
     hipcc = hipcc_path()
-    bdir = build_dir or os.path.join(HERE, "_build")
+    lib_path = LIB_PATH
+    bdir = os.path.join(HERE, "_build")
     os.makedirs(bdir, exist_ok=True)
     objs = [os.path.join(bdir, s.replace(".hip", ".o")) for s in SOURCES]
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        results = list(ex.map(lambda so: _compile(hipcc, so[0], so[1], extra_flags), zip(SOURCES, objs)))
+        results = list(ex.map(lambda so: _compile(hipcc, so[0], so[1]), zip(SOURCES, objs)))
     for src, rc, out, cmd in results:
         noise = "packed-fp32-ops' is not a recognized feature"
         shown = "\n".join(l for l in out.splitlines() if noise not in l)

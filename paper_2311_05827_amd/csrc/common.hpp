@@ -61,6 +61,9 @@ struct UPlan {
   int64_t cps;         // U_SEGMENTED: chunks per segment
   int64_t chunk_vecs;  // U_SEGMENTED: 16-byte vectors per chunk
   int64_t items;       // U_SEGMENTED: n*C*cps partial maxima
+  int col_tx;          // U_GENERIC: column threads per workgroup of the column pass (a power of two)
+  int64_t col_grid_x;  // U_GENERIC: workgroups across the columns
+  int col_grid_y;      // U_GENERIC: row blocks = maxima kept per column
   bool fast;           // vector path usable (every 16-byte vector lies inside one range group)
   size_t off_rtab;     // byte offset of the per-channel reciprocal table in the workspace
   size_t bytes;        // workspace bytes
@@ -108,63 +111,25 @@ typedef uint32_t v4u_t __attribute__((ext_vector_type(4)));
 // kernel.  Streaming (non-temporal) stores let output lines drain to HBM while the kernel that
 // wrote them still runs, instead of sitting dirty in L2 / the memory-side cache and stealing
 // bandwidth from the next kernel; streaming loads keep single-use input from evicting them.
-// The -D switches exist for tuning sweeps only.
-#ifndef ACCEPT_NT_STORE
-#define ACCEPT_NT_STORE 1
-#endif
-#ifndef ACCEPT_NT_LOAD
-#define ACCEPT_NT_LOAD 1
-#endif
-
 __device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ uint4 load16_stream(const void* p) {
-#if ACCEPT_NT_LOAD
   const v4u_t v = __builtin_nontemporal_load(reinterpret_cast<const v4u_t*>(p));
   return make_uint4(v.x, v.y, v.z, v.w);
-#else
-  return load16(p);
-#endif
 }
 __device__ __forceinline__ void store16_stream(void* p, uint4 v) {
-#if ACCEPT_NT_STORE
   const v4u_t u = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(u, reinterpret_cast<v4u_t*>(p));
-#else
-  *reinterpret_cast<uint4*>(p) = v;
-#endif
 }
 
-// NDW consecutive dwords, aligned to 16 bytes when NDW % 4 == 0, to 8 when NDW % 2 == 0, else 4.
-#ifndef ACCEPT_PAYLOAD_STREAM
-#define ACCEPT_PAYLOAD_STREAM 0
-#endif
-typedef uint32_t v2u_t __attribute__((ext_vector_type(2)));
+// NDW consecutive dwords of payload (plain stores: streaming stores of the payload gained nothing),
+// aligned to 16 bytes when NDW % 4 == 0, to 8 when NDW % 2 == 0, else 4.
 template <int NDW>
 __device__ __forceinline__ void store_dwords(uint32_t* p, const uint32_t (&v)[NDW]) {
-#if ACCEPT_PAYLOAD_STREAM
-  if constexpr (NDW % 4 == 0) {
-#pragma unroll
-    for (int i = 0; i < NDW; i += 4) {
-      const v4u_t u = {v[i], v[i + 1], v[i + 2], v[i + 3]};
-      __builtin_nontemporal_store(u, reinterpret_cast<v4u_t*>(p + i));
-    }
-  } else if constexpr (NDW % 2 == 0) {
-#pragma unroll
-    for (int i = 0; i < NDW; i += 2) {
-      const v2u_t u = {v[i], v[i + 1]};
-      __builtin_nontemporal_store(u, reinterpret_cast<v2u_t*>(p + i));
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < NDW; ++i) __builtin_nontemporal_store(v[i], p + i);
-  }
-#else
   struct alignas((NDW % 4 == 0) ? 16 : (NDW % 2 == 0) ? 8 : 4) Block { uint32_t w[NDW]; };
   Block b;
 #pragma unroll
   for (int i = 0; i < NDW; ++i) b.w[i] = v[i];
   *reinterpret_cast<Block*>(p) = b;
-#endif
 }
 
 __device__ __forceinline__ void widen(const uint4 v, float (&f)[4]) {

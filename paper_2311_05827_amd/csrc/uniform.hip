@@ -14,34 +14,18 @@ namespace accept {
 
 namespace {
 
-#ifndef ACCEPT_RANGE_STREAM
-#define ACCEPT_RANGE_STREAM 1  // the range pass reads with streaming loads as well (measured best in the step mix)
-#endif
-
+// The range pass reads with streaming loads as well: measured best in a mix of calls (cacheable
+// loads make the quantize pass a little faster and the range pass, and the mix, slower).
 template <typename T, int V>
 __device__ __forceinline__ void load_range(const T* p, float (&f)[V]) {
-#if ACCEPT_RANGE_STREAM
   load_vec_stream(p, f);
-#else
-  load_vec(p, f);
-#endif
 }
 
 constexpr float kTinyRange = 0x1p-100f;     // smaller ranges count as an all-zero tensor
 constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to integer, half to even
-// Launch-shape constants; the -D overrides exist for tuning sweeps only.
-#ifndef ACCEPT_RANGE_GRID
-#define ACCEPT_RANGE_GRID 512
-#endif
-#ifndef ACCEPT_QUANT_GRID
-#define ACCEPT_QUANT_GRID 2048
-#endif
-#ifndef ACCEPT_DEQUANT_GRID
-#define ACCEPT_DEQUANT_GRID 8192
-#endif
-constexpr int kRangeGridMax = ACCEPT_RANGE_GRID;     // partial maxima of the per-tensor range pass
-constexpr int kQuantGridMax = ACCEPT_QUANT_GRID;     // workgroups of the quantize+pack kernel
-constexpr int kDequantGridMax = ACCEPT_DEQUANT_GRID;
+constexpr int kRangeGridMax = 512;     // partial maxima of the per-tensor range pass
+constexpr int kQuantGridMax = 2048;    // workgroups of the quantize+pack kernel
+constexpr int kDequantGridMax = 8192;
 static_assert(kRangeGridMax <= 4096, "the workspace holds at most 4096 partial maxima");
 
 // s = c / L and r = L / c as correctly rounded float32 quotients (a float64 quotient of two
@@ -168,18 +152,80 @@ __global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restr
   }
 }
 
-// Any channel geometry: one atomic max per element on the channel's slot (bit patterns of
-// non-negative floats order like unsigned integers).  Slow; correctness path only.
-__global__ void zero_u32_kernel(uint32_t* p, int64_t count) {
-  for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < count; i += int64_t(gridDim.x) * blockDim.x)
-    p[i] = 0u;
+// One range per channel, any other geometry (short segments, segments that no 16-byte vector
+// respects; with one element per segment this is a channels-last tensor): two stages, no atomics.
+// Stage 1 works on columns: a thread owns CV adjacent columns (a 16-byte vector when rows keep
+// vectors aligned, else one column), walks down its share of the rows and keeps the columns'
+// maxima; the workgroup is TX column-threads wide (consecutive lanes read consecutive vectors of
+// a row) and 256/TX rows high; its threads of equal column meet in local memory and the
+// workgroup writes one maximum per column: colmax[by * m + column].  Stage 2 folds the columns
+// of a channel and the row blocks.
+template <typename T, int CV>
+__global__ __launch_bounds__(kBlock) void range_columns_kernel(const T* __restrict__ x, int64_t n, int64_t m,
+                                                                int tx_threads, float* __restrict__ colmax) {
+  __shared__ float red[kBlock][CV];
+  const int ty_threads = kBlock / tx_threads;
+  const int tx = threadIdx.x % tx_threads, ty = threadIdx.x / tx_threads;
+  const int64_t ncv = m / CV;
+  const int64_t cv = int64_t(blockIdx.x) * tx_threads + tx;
+  float c[CV];
+#pragma unroll
+  for (int e = 0; e < CV; ++e) c[e] = 0.0f;
+  if (cv < ncv) {
+    const int64_t row_step = int64_t(gridDim.y) * ty_threads;
+    int64_t r = int64_t(blockIdx.y) * ty_threads + ty;
+    const T* col = x + cv * CV;
+    for (; r + 3 * row_step < n; r += 4 * row_step) {  // four loads in flight
+      float f[4][CV];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if constexpr (CV > 1) load_range<T, CV>(col + (r + u * row_step) * m, f[u]);
+        else f[u][0] = load_one(col + (r + u * row_step) * m);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < CV; ++e) c[e] = fmaxf(c[e], fabsf(f[u][e]));
+    }
+    for (; r < n; r += row_step) {
+      float f[CV];
+      if constexpr (CV > 1) load_range<T, CV>(col + r * m, f);
+      else f[0] = load_one(col + r * m);
+#pragma unroll
+      for (int e = 0; e < CV; ++e) c[e] = fmaxf(c[e], fabsf(f[e]));
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < CV; ++e) red[threadIdx.x][e] = c[e];
+  __syncthreads();
+  if (ty == 0 && cv < ncv) {
+    for (int y = 1; y < ty_threads; ++y)
+#pragma unroll
+      for (int e = 0; e < CV; ++e) c[e] = fmaxf(c[e], red[y * tx_threads + tx][e]);
+#pragma unroll
+    for (int e = 0; e < CV; ++e) colmax[int64_t(blockIdx.y) * m + cv * CV + e] = c[e];
+  }
 }
-template <typename T>
-__global__ __launch_bounds__(kBlock) void range_generic_kernel(const T* __restrict__ x, int64_t N, int64_t m,
-                                                                int64_t seg_len, uint32_t* __restrict__ chanmax) {
-  for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < N; i += int64_t(gridDim.x) * kBlock) {
-    const int64_t ch = (i % m) / seg_len;
-    atomicMax(chanmax + ch, f32_as_u32(fabsf(load_one(x + i))));
+
+// Stage 2 and U1b: one wavefront per channel takes the maximum over the channel's seg_len
+// columns in all nby row blocks, writes s to the header and the reciprocal to the table.
+__global__ __launch_bounds__(kWave) void range_columns_finalize_kernel(const float* __restrict__ colmax, int64_t m,
+                                                                        int64_t seg_len, int nby, int k,
+                                                                        float* __restrict__ header,
+                                                                        float* __restrict__ rtab) {
+  const int64_t ch = blockIdx.x;
+  float c = 0.0f;
+  const int64_t per = seg_len * nby;
+  for (int64_t j = threadIdx.x; j < per; j += kWave) {
+    const int64_t by = j / seg_len;
+    c = fmaxf(c, colmax[by * m + ch * seg_len + (j - by * seg_len)]);
+  }
+  c = wave_max(c);
+  if (threadIdx.x == 0) {
+    float s, r;
+    scale_from_range(c, k, s, r);
+    header[ch] = s;
+    rtab[ch] = r;
   }
 }
 
@@ -746,22 +792,27 @@ hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, floa
     hipLaunchKernelGGL((range_segments_kernel<T>), dim3(grid), dim3(kBlock), 0, s, x, p.items, p.cps,
                        p.seg_len / p.vec, p.chunk_vecs, partials);
   } else {
-    const int zgrid = int((p.C + kBlock - 1) / kBlock < 1024 ? (p.C + kBlock - 1) / kBlock : 1024);
-    hipLaunchKernelGGL(zero_u32_kernel, dim3(zgrid), dim3(kBlock), 0, s, reinterpret_cast<uint32_t*>(partials), p.C);
-    const int64_t blocks = (p.N + kBlock - 1) / kBlock;
-    const int grid = int(blocks < 16384 ? blocks : 16384);
-    hipLaunchKernelGGL((range_generic_kernel<T>), dim3(grid), dim3(kBlock), 0, s, x, p.N, p.m, p.seg_len,
-                       reinterpret_cast<uint32_t*>(partials));
+    const dim3 grid(unsigned(p.col_grid_x), unsigned(p.col_grid_y));
+    if (p.m % Elem<T>::VEC == 0)
+      hipLaunchKernelGGL((range_columns_kernel<T, Elem<T>::VEC>), grid, dim3(kBlock), 0, s, x, d.n, p.m, p.col_tx,
+                         partials);
+    else
+      hipLaunchKernelGGL((range_columns_kernel<T, 1>), grid, dim3(kBlock), 0, s, x, d.n, p.m, p.col_tx, partials);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   mark(tm, s);
   const bool plain = d.layout != ACCEPT_LAYOUT_PACKED;
-  if (p.mode != U_TENSOR || plain) {
-    // U_GENERIC stores one maximum per channel: finalize reads it as a 1 x C x 1 table; the
-    // per-tensor pass leaves range_grid maxima: one row, one channel, range_grid chunks.
+  if (p.mode == U_GENERIC) {
+    hipLaunchKernelGGL(range_columns_finalize_kernel, dim3(unsigned(p.C)), dim3(kWave), 0, s, partials, p.m, p.seg_len,
+                       p.col_grid_y, d.bits, header, rtab);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    mark(tm, s);
+  } else if (p.mode != U_TENSOR || plain) {
+    // the per-tensor pass leaves range_grid maxima: one row, one channel, range_grid chunks
     const int64_t rows = p.mode == U_SEGMENTED ? d.n : 1;
-    const int64_t cps = p.mode == U_SEGMENTED ? p.cps : (p.mode == U_TENSOR ? p.range_grid : 1);
+    const int64_t cps = p.mode == U_SEGMENTED ? p.cps : p.range_grid;
     hipLaunchKernelGGL(range_finalize_kernel, dim3(unsigned(p.C)), dim3(kWave), 0, s, partials, rows, p.C, cps,
                        d.bits, header, rtab);
     e = hipGetLastError();
@@ -909,7 +960,23 @@ UPlan make_uplan(const accept_desc& d) {
   } else {
     p.mode = U_GENERIC;
     p.fast = (p.seg_len % p.vec == 0);
-    partial_bytes = size_t(p.C) * sizeof(uint32_t);
+    // column pass: threads own vectors of columns when every row keeps them aligned, else columns
+    const int64_t ncv = (d.m % p.vec == 0) ? d.m / p.vec : d.m;
+    int tx = 1;
+    while (tx < kBlock && tx < ncv) tx *= 2;
+    p.col_tx = tx;
+    const int64_t ty = kBlock / tx;
+    const int64_t gx = (ncv + tx - 1) / tx;
+    int64_t gy = (d.n + ty - 1) / ty;                      // at most one row per thread row
+    const int64_t want = gx >= 2048 ? 1 : 2048 / gx;       // about 2048 workgroups in all
+    if (gy > want) gy = want;
+    const int64_t cap = (int64_t(16) << 20) / d.m;         // at most 64 MiB of column maxima
+    if (gy > cap) gy = cap;
+    if (gy < 1) gy = 1;
+    if (gy > 65535) gy = 65535;
+    p.col_grid_x = gx;
+    p.col_grid_y = int(gy);
+    partial_bytes = size_t(gy) * size_t(d.m) * sizeof(float);
   }
   p.off_rtab = kCtrlBytes + (partial_bytes + 255) / 256 * 256;
   p.bytes = p.off_rtab + (size_t(p.C) * sizeof(float) + 255) / 256 * 256;

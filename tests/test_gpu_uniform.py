@@ -126,7 +126,7 @@ def test_per_channel_segmented(A, k, in_bf16):
 
 @pytest.mark.parametrize("k", [3, 4, 8])
 def test_per_channel_generic_geometries(A, k):
-    # short aligned segments (vector quantize path, atomic range pass)
+    # short aligned segments (vector quantize path, column range pass)
     x = si.make_shape("relu_lognormal_chgain", (6, 10, 12), 50 + k)
     run_case(A, x, k, 6, 120, channels=10, tag="seg12")
     x = si.make_shape("relu_lognormal_chgain", (40, 64, 8, 8), 51 + k)
@@ -140,6 +140,14 @@ def test_per_channel_generic_geometries(A, k):
     # one element per channel (channels-last 2-D tensor)
     x = si.make_shape("grad", (50, 96), 54 + k)
     run_case(A, x, k, 50, 96, channels=96, tag="seg1")
+    # channels-last with many rows (several row blocks in the column pass), aligned and not
+    x = si.make_shape("grad_outliers", (5000, 256), 55 + k)
+    run_case(A, x, k, 5000, 256, channels=256, tag="channels-last 256")
+    run_case(A, x, k, 5000, 256, channels=256, in_bf16=True, out_bf16=True, tag="channels-last 256 bf16")
+    x = si.make_shape("relu_lognormal", (3001, 30, 11), 56 + k)
+    run_case(A, x, k, 3001, 330, channels=30, tag="seg11 unaligned rows")
+    x = si.make_shape("student_t3", (37, 1300, 3), 57 + k)
+    run_case(A, x, k, 37, 3900, channels=1300, tag="seg3 wide")
 
 
 @pytest.mark.parametrize("k", [2, 4, 7, 8])
