@@ -13,7 +13,12 @@ that nothing a call reads was produced or read by the previous ~1 GB of traffic 
 value = GB/s of uncompressed fp32 bytes through the step's four calls; the breakdown holds
 each call's own rate and its algorithmic fraction of the 8 TB/s HBM peak; "roofline"
 describes the dominant kernel from HIP-event stage timings taken inside this run;
-"cpu_baseline" is the CPU oracle timed on a bounded sample of the same workload.
+"cells" holds every cell of the benchmark configuration as its description words it (per
+tensor and per channel, 4/6/8 bits, fp32 and bf16, the gradient tensor, the forward widths
+2/3/4) as single calls: cold median and minimum, warm (back-to-back) median, and the
+algorithmic fraction of the HBM peak; "cpu_baseline" is the CPU oracle timed on the same
+workload (one thread, as it stands), "cpu_baseline_all_cores" the same oracle functions run on
+row chunks by a pool of processes.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--sweep]
 """
@@ -88,8 +93,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--sweep", action="store_true", help="also time every (config, scheme, k) cell; table on stderr")
-    ap.add_argument("--sweep-json", default=None, help="with --sweep: also write the table to this JSON file")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the cells of all five configurations (default: those of the benchmark configuration)")
+    ap.add_argument("--sweep-json", default=None, help="also write the cells to this JSON file")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--graph", action="store_true",
                     help="replay a captured HIP graph of two steps instead of launching every call eagerly "
@@ -312,12 +318,21 @@ def main():
         "kernels": kernels,
     }
 
-    cpu = None
+    # the same for whole calls (every kernel the call launches: range + quantize_pack, encode +
+    # finalize), from the in-mix timings above
+    call_roofline = {name: {"bound": "hbm", "achieved": round(v["alg_bytes"] / (v["ms"] * 1e-3) / 1e9, 1),
+                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": v["alg_hbm_frac"]}
+                     for name, v in breakdown.items()}
+
+    cpu = cpu_all = None
     if not args.no_cpu:
         cpu = cpu_baseline(np, act_np, grad_np, n, m)
+        cpu_all = cpu_baseline_all_cores(np, act_np, grad_np, n, m)
 
-    if args.sweep:
-        sweep(A, torch, si, np, args.sweep_json)
+    cells = run_cells(A, torch, si, ALL_CELLS if args.sweep else CFG4_CELLS)
+    if args.sweep_json:
+        with open(args.sweep_json, "w") as f:
+            json.dump(cells, f, indent=1)
 
     out = {
         "metric": METRIC,
@@ -343,9 +358,104 @@ def main():
         "hbm_frac_of_value": round(value / HBM_PEAK_GBPS, 4),
         "breakdown": breakdown,
         "roofline": roofline,
+        "roofline_calls": call_roofline,
+        "cells": cells,
         "cpu_baseline": cpu,
+        "cpu_baseline_all_cores": cpu_all,
     }
     print(json.dumps(out), flush=True)
+
+
+def _pool_uniform_max(args):
+    from oracle import accept_oracle as orc
+    lo, hi = args
+    return float(orc.uniform_range(_G["grad"][lo:hi], hi - lo, _G["m"])[0])
+
+
+def _pool_uniform_pack(args):
+    from oracle import accept_oracle as orc
+    lo, hi, r = args
+    import numpy as np
+    rows = hi - lo
+    q = orc.uniform_quantize(_G["grad"][lo:hi], np.array([r], np.float32), K_BWD, rows, _G["m"])
+    pl = orc.pack_stream(orc.uniform_codes(q, K_BWD), K_BWD)
+    _G["upay"][lo * _G["m"] * K_BWD // 8: hi * _G["m"] * K_BWD // 8] = pl
+    return pl.size
+
+
+def _pool_uniform_unpack(args):
+    from oracle import accept_oracle as orc
+    lo, hi, s = args
+    import numpy as np
+    rows = hi - lo
+    pl = _G["upay"][lo * _G["m"] * K_BWD // 8: hi * _G["m"] * K_BWD // 8]
+    xh = orc.uniform_decompress(np.array([s], "<f4").tobytes(), pl, K_BWD, rows, _G["m"])
+    return float(xh[0])
+
+
+def _pool_mbq_encode(args):
+    from oracle import accept_oracle as orc
+    lo, hi = args
+    rows = hi - lo
+    x = _G["act"][lo:hi]
+    code = orc.mbq_assign(x, _G["alpha"])
+    pl = orc.mbq_pack(code, K_FWD, rows, _G["m"])
+    _G["mpay"][(lo // 8) * _G["m"] * K_FWD: (hi // 8) * _G["m"] * K_FWD] = pl
+    return orc.mbq_stats(x, code, K_FWD)
+
+
+def _pool_mbq_decode(args):
+    from oracle import accept_oracle as orc
+    lo, hi, header = args
+    rows = hi - lo
+    pl = _G["mpay"][(lo // 8) * _G["m"] * K_FWD: (hi // 8) * _G["m"] * K_FWD]
+    return float(orc.mbq_decompress(header, pl, K_FWD, rows, _G["m"])[0])
+
+
+_G = {}
+
+
+def cpu_baseline_all_cores(np, act_np, grad_np, n, m):
+    """The oracle's own functions on chunks of eight batch rows, run by a pool of processes (the
+    chunks' bit streams and bit planes concatenate; the range and the least-squares sums are
+    combined between the passes).  Forked workers see the tensors without copying them."""
+    import multiprocessing as mp
+    from oracle import accept_oracle as orc
+    cores = min(16, os.cpu_count() or 1)
+    shm = mp.get_context("fork")
+    _G.update(act=act_np.reshape(n, m), grad=grad_np.reshape(n, m), m=m)
+    _G["upay"] = np.frombuffer(mp.RawArray("B", n * m * K_BWD // 8), dtype=np.uint8)
+    _G["mpay"] = np.frombuffer(mp.RawArray("B", ((n + 7) // 8) * m * K_FWD), dtype=np.uint8)
+    _G["alpha"], _ = orc.mbq_residue_init(_G["act"][:8], K_FWD)  # any plausible previous alpha (not timed)
+    chunks = [(lo, min(lo + 8, n)) for lo in range(0, n, 8)]
+    N = n * m
+    with shm.Pool(cores) as pool:
+        pool.map(_pool_uniform_max, chunks[:cores])  # start the workers before the clock
+        t0 = time.perf_counter()
+        # forward features: assign + pack + sums per chunk, then the update; decode per chunk
+        stats = pool.map(_pool_mbq_encode, chunks)
+        G = sum(s[0] for s in stats); h = sum(s[1] for s in stats)
+        Sb = sum(s[2] for s in stats); Sx = sum(s[3] for s in stats)
+        alpha_t, _ = orc.mbq_alpha_update(_G["alpha"], G, h, 1, N)
+        mq = orc.mbq_mean_error(alpha_t, Sb, Sx, N)
+        header = np.concatenate([alpha_t, np.array([mq], np.float32)]).astype("<f4").tobytes()
+        pool.map(_pool_mbq_decode, [(lo, hi, header) for lo, hi in chunks])
+        # backward gradients: range per chunk, then quantize + pack per chunk; decode per chunk
+        c = np.float32(max(pool.map(_pool_uniform_max, chunks)))
+        s_, r_ = orc.uniform_scale(np.array([c], np.float32), K_BWD)
+        pool.map(_pool_uniform_pack, [(lo, hi, float(r_[0])) for lo, hi in chunks])
+        pool.map(_pool_uniform_unpack, [(lo, hi, float(s_[0])) for lo, hi in chunks])
+        dt = time.perf_counter() - t0
+    nbytes = 4 * N * 4
+    log("cpu oracle, %d processes: %.2fs for the same four calls" % (cores, dt))
+    return {
+        "value": round(nbytes / dt / 1e9, 4),
+        "unit": "GB/s",
+        "cores": cores,
+        "kind": "oracle functions on 8-row chunks, process pool",
+        "sample": "the whole workload: all %d batch rows of the same two tensors, the same four calls" % n,
+        "seconds": round(dt, 3),
+    }
 
 
 def cpu_baseline(np, act_np, grad_np, n, m):
@@ -377,83 +487,120 @@ def cpu_baseline(np, act_np, grad_np, n, m):
     }
 
 
-def sweep(A, torch, si, np, out_path=None):
-    """Cold-input timings of every (config, scheme, k, dtype, range mode) cell; stderr table."""
-    dev = torch.device("cuda:0")
-    scratch = torch.zeros(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB, read-only sweep between calls
+class CellTimer:
+    """Single-call timings of one (tensor, scheme, k, channels, dtype) cell."""
 
-    def flush():
-        scratch.sum()
+    def __init__(self, A, torch, dev):
+        self.A, self.torch, self.dev = A, torch, dev
+        self.scratch = torch.zeros(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB, read between cold calls
 
-    def timeit(fn, reps=20):
+    def _cold(self, fn, reps):
+        torch = self.torch
         fn(); torch.cuda.synchronize()
-        tot = []
+        t = []
         for _ in range(reps):
-            flush()
+            self.scratch.sum()          # read-only 1 GiB: nothing of the call's data is left in a cache
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(); fn(); e1.record(); e1.synchronize()
-            tot.append(e0.elapsed_time(e1))
-        tot.sort()
-        return tot[len(tot) // 2]
+            t.append(e0.elapsed_time(e1))
+        t.sort()
+        return t[len(t) // 2], t[0]
 
+    def _warm(self, fn, reps):
+        torch = self.torch
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def cell(self, name, x32, x16, n, m, scheme, k, C, bf, reps=15):
+        A, torch, dev = self.A, self.torch, self.dev
+        N = n * m
+        x = x16 if bf else x32
+        b = 2 if bf else 4
+        tcode = A.BF16 if bf else A.F32
+        layout = {"b": A.LAYOUT_BATCH, "u": A.LAYOUT_UNENCODED}.get(scheme[1:], A.LAYOUT_PACKED)
+        if scheme[0] == "U":
+            d = A.make_desc(A.UNIFORM, k, n, m, channels=C, in_dtype=tcode, out_dtype=tcode, layout=layout,
+                            rounding=A.ROUND_STOCHASTIC if scheme == "Us" else A.ROUND_NEAREST_EVEN, seed=7)
+            alpha = None
+        else:
+            d = A.make_desc(A.MBQ, k, n, m, t=1, in_dtype=tcode, out_dtype=tcode, layout=layout)
+            alpha = A.accept_mbq_init(d, x)
+        # algorithmic bytes of the call: the input (twice for scheme U: range pass, quantize pass),
+        # the header and the payload of this layout one way; the same plus the output back
+        hb, pb = A.accept_packed_size(d)
+        cb = (2 if scheme[0] == "U" else 1) * N * b + hb + pb
+        db = hb + pb + N * b
+        h, p, w = A.alloc_outputs(d, dev)
+        out = torch.empty(N, dtype=torch.bfloat16 if bf else torch.float32, device=dev)
+        comp = lambda: A.accept_compress(d, x, alpha_prev=alpha, header=h, payload=p, workspace=w)
+        deco = lambda: A.accept_decompress(d, h, p, out=out)
+        tc, tc_min = self._cold(comp, reps)
+        td, td_min = self._cold(deco, reps)
+        tcw, tdw = self._warm(comp, reps), self._warm(deco, reps)
+        frac = lambda nbytes, ms: round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4)
+        return dict(config=name, scheme=scheme, k=k, channels=C, dtype="bf16" if bf else "f32",
+                    compress_us=round(tc * 1e3, 2), compress_us_min=round(tc_min * 1e3, 2),
+                    compress_us_warm=round(tcw * 1e3, 2),
+                    decompress_us=round(td * 1e3, 2), decompress_us_min=round(td_min * 1e3, 2),
+                    decompress_us_warm=round(tdw * 1e3, 2),
+                    compress_in_GBps=round(N * b / tc / 1e6, 1), decompress_out_GBps=round(N * b / td / 1e6, 1),
+                    compress_alg_bytes=cb, decompress_alg_bytes=db,
+                    compress_alg_frac=frac(cb, tc), decompress_alg_frac=frac(db, td),
+                    compress_alg_frac_best=frac(cb, tc_min), decompress_alg_frac_best=frac(db, td_min))
+
+
+CFG4_CELLS = [
+    ("cfg4_act", [("U", k, c, b) for k in (4, 6, 8) for c in (0, 256) for b in (False, True)]
+     + [("M", k, 0, False) for k in (2, 3, 4)] + [("M", 4, 0, True)]),
+    ("cfg4_grad", [("U", k, c, False) for k in (4, 6, 8) for c in (0, 256)]),
+]
+ALL_CELLS = [
+    ("cfg1_act", [("U", 8, 0, False), ("M", 2, 0, False), ("M", 3, 0, False), ("M", 4, 0, False)]),
+    ("cfg2_grad", [("U", 4, 0, False), ("U", 2, 0, False)]),
+    ("cfg3_act", [("U", k, 0, False) for k in range(2, 9)] + [("M", k, 0, False) for k in (2, 3, 4)]),
+    ("cfg4_act", CFG4_CELLS[0][1] + [("M", 2, 0, True), ("Mu", 4, 0, False)]),  # Mu: one byte per binary base
+    ("cfg4_grad", CFG4_CELLS[1][1]
+     + [("Us", k, 0, False) for k in (4, 8)]          # Us: stochastic rounding
+     + [("Ub", 4, 0, False), ("Uu", 4, 0, False)]),   # Ub: batch-pair layout, Uu: one byte per code
+    ("cfg5_hidden", [("U", k, 0, False) for k in (3, 5, 6, 7)] + [("M", 3, 0, False)]),
+    ("cfg5_grad", [("U", k, 0, False) for k in (3, 5, 6, 7)]),
+]
+
+
+def run_cells(A, torch, si, plans, extra_views=True):
+    """Time the cells of `plans`; table on stderr, list of dicts returned."""
+    dev = torch.device("cuda:0")
+    ct = CellTimer(A, torch, dev)
     cells = []
-    plans = [
-        ("cfg1_act", [("U", 8, 0, False), ("M", 2, 0, False), ("M", 3, 0, False), ("M", 4, 0, False)]),
-        ("cfg2_grad", [("U", 4, 0, False), ("U", 2, 0, False)]),
-        ("cfg3_act", [("U", k, 0, False) for k in range(2, 9)] + [("M", k, 0, False) for k in (2, 3, 4)]),
-        ("cfg4_act", [("U", k, c, b) for k in (4, 6, 8) for c in (0, 256) for b in (False, True)]
-         + [("M", k, 0, False) for k in (2, 3, 4)] + [("M", k, 0, True) for k in (2, 4)]
-         + [("Mu", 4, 0, False)]),  # Mu: one byte per binary base
-        ("cfg4_grad", [("U", k, c, False) for k in (4, 6, 8) for c in (0, 256)]
-         + [("Us", k, 0, False) for k in (4, 8)]      # Us: stochastic rounding
-         + [("Ub", 4, 0, False), ("Uu", 4, 0, False)]),  # Ub: batch-pair layout, Uu: one byte per code
-        ("cfg5_hidden", [("U", k, 0, False) for k in (3, 5, 6, 7)] + [("M", 3, 0, False)]),
-        ("cfg5_grad", [("U", k, 0, False) for k in (3, 5, 6, 7)]),
-    ]
-    log("%-12s %-2s %1s %4s %5s | %9s %9s %7s | %9s %9s %7s" % (
-        "config", "S", "k", "C", "dtype", "comp_us", "in_GB/s", "alg%", "decomp_us", "out_GB/s", "alg%"))
+    log("%-12s %-2s %1s %4s %5s | %8s %8s %8s %6s | %8s %8s %8s %6s" % (
+        "config", "S", "k", "C", "dtype", "comp_us", "min", "warm", "alg%", "dec_us", "min", "warm", "alg%"))
+
+    def show(c):
+        log("%-12s %-2s %1d %4d %5s | %8.1f %8.1f %8.1f %5.1f%% | %8.1f %8.1f %8.1f %5.1f%%" % (
+            c["config"], c["scheme"], c["k"], c["channels"], c["dtype"], c["compress_us"], c["compress_us_min"],
+            c["compress_us_warm"], 100 * c["compress_alg_frac"], c["decompress_us"], c["decompress_us_min"],
+            c["decompress_us_warm"], 100 * c["decompress_alg_frac"]))
+
     for name, cases in plans:
         x_np = si.make(name)
         n, m = si.as_nm(x_np)
-        N = n * m
         x32 = torch.from_numpy(x_np.reshape(-1)).to(dev)
         x16 = x32.to(torch.bfloat16)
         for scheme, k, C, bf in cases:
-            x = x16 if bf else x32
-            b = 2 if bf else 4
-            layout = {"b": A.LAYOUT_BATCH, "u": A.LAYOUT_UNENCODED}.get(scheme[1:], A.LAYOUT_PACKED)
-            if scheme[0] == "U":
-                d = A.make_desc(A.UNIFORM, k, n, m, channels=C, in_dtype=A.BF16 if bf else A.F32,
-                                out_dtype=A.BF16 if bf else A.F32, layout=layout,
-                                rounding=A.ROUND_STOCHASTIC if scheme == "Us" else A.ROUND_NEAREST_EVEN, seed=7)
-                alpha = None
-            else:
-                d = A.make_desc(A.MBQ, k, n, m, t=1, in_dtype=A.BF16 if bf else A.F32,
-                                out_dtype=A.BF16 if bf else A.F32, layout=layout)
-                alpha = A.accept_mbq_init(d, x)
-            # algorithmic bytes of the call: the input (twice for scheme U: range pass, quantize
-            # pass), the header and the payload of this layout one way; the same plus the output back
-            hb, pb = A.accept_packed_size(d)
-            cb = (2 if scheme[0] == "U" else 1) * N * b + hb + pb
-            db = hb + pb + N * b
-            h, p, w = A.alloc_outputs(d, dev)
-            out = torch.empty(N, dtype=torch.bfloat16 if bf else torch.float32, device=dev)
-            tc = timeit(lambda: A.accept_compress(d, x, alpha_prev=alpha, header=h, payload=p, workspace=w))
-            td = timeit(lambda: A.accept_decompress(d, h, p, out=out))
-            cell = dict(config=name, scheme=scheme, k=k, channels=C, dtype="bf16" if bf else "f32",
-                        compress_us=round(tc * 1e3, 2), decompress_us=round(td * 1e3, 2),
-                        compress_in_GBps=round(N * b / tc / 1e6, 1), decompress_out_GBps=round(N * b / td / 1e6, 1),
-                        compress_alg_frac=round(cb / tc / 1e6 / HBM_PEAK_GBPS, 4),
-                        decompress_alg_frac=round(db / td / 1e6 / HBM_PEAK_GBPS, 4))
-            cells.append(cell)
-            log("%-12s %-2s %1d %4d %5s | %9.1f %9.1f %6.1f%% | %9.1f %9.1f %6.1f%%" % (
-                name, scheme, k, C, cell["dtype"], tc * 1e3, cell["compress_in_GBps"],
-                100 * cell["compress_alg_frac"], td * 1e3, cell["decompress_out_GBps"],
-                100 * cell["decompress_alg_frac"]))
+            c = ct.cell(name, x32, x16, n, m, scheme, k, C, bf)
+            cells.append(c); show(c)
+        if extra_views and name == "cfg4_grad":
+            # the same bytes read as a channels-last tensor (64*3136 rows of 256 channels): one range
+            # per element of a row, the geometry the column range pass is for
+            c = ct.cell("cfg4_grad_nhwc", x32, x16, n * (m // 256), 256, "U", 8, 256, False)
+            cells.append(c); show(c)
         del x32, x16
-    if out_path:
-        with open(out_path, "w") as f:
-            json.dump(cells, f, indent=1)
+    return cells
 
 
 if __name__ == "__main__":
