@@ -23,9 +23,10 @@
  *
  * Memory: every pointer named *_dev is DEVICE memory of the current HIP device; the
  * descriptor and the size outputs are HOST memory.  The caller allocates and owns all
- * buffers; the library allocates no device memory, keeps no state between calls, enqueues
- * its kernels on the given stream and returns without waiting for them (except where a
- * function says that it synchronises).
+ * buffers; the library allocates no device memory, keeps no state between calls (what a
+ * later call needs stays in the caller's workspace), enqueues its kernels on the given stream
+ * and returns without waiting for them.  The measurement entry points that bracket kernels
+ * with events and wait are declared apart, in accept_profile.h.
  *
  * Errors: every function returns an accept_status; nothing is thrown across the ABI.
  * When a call fails validation, no kernel is launched and no output byte is written.
@@ -196,26 +197,6 @@ accept_status accept_mbq_init(const accept_desc* desc, const void* x_dev, float*
  */
 accept_status accept_mbq_compress_first(const accept_desc* desc, const void* x_dev, void* header_dev,
                                         void* payload_dev, void* workspace_dev, void* hip_stream);
-
-/*
- * Measurement variants: same work as accept_compress / accept_decompress, but every
- * kernel the call launches is bracketed by HIP events on the given stream; the call then
- * WAITS for the last event and writes each stage's duration in milliseconds to the host
- * array stage_ms[0..*n_stages) (capacity ACCEPT_MAX_STAGES).  Stage order:
- *   UNIFORM compress: range, [range finalize], quantize+pack;   MBQ compress: the one kernel;
- *   decompress: the one kernel.
- * For benchmarks only; creates and destroys its events on every call.
- */
-enum { ACCEPT_MAX_STAGES = 8 };
-accept_status accept_compress_timed(const accept_desc* desc, const void* x_dev, const float* alpha_prev_dev,
-                                    void* header_dev, void* payload_dev, void* workspace_dev, void* hip_stream,
-                                    float* stage_ms, int* n_stages);
-accept_status accept_decompress_timed(const accept_desc* desc, const void* header_dev, const void* payload_dev,
-                                      void* xhat_dev, void* hip_stream, float* stage_ms, int* n_stages);
-
-/* Name of stage i of the call accept_*_timed would make for this descriptor
- * (is_decompress = 0/1); null when i is out of range.  Host-only. */
-const char* accept_stage_name(const accept_desc* desc, int is_decompress, int i);
 
 /*
  * Adaptive bit width.  direction 0 (forward): 2, then +1 per learning-rate change, at

@@ -26,8 +26,8 @@ STATUS_NAMES = {0: "ACCEPT_OK", 1: "ACCEPT_ERR_INVALID_ARG", 2: "ACCEPT_ERR_UNSU
 class AcceptError(RuntimeError):
     def __init__(self, status, where):
         self.status = int(status)
-        super().__init__("%s failed: %s (%s)" % (where, STATUS_NAMES.get(self.status, self.status),
-                                                  status_string(self.status)))
+        super().__init__("%s: %s (%s)" % (where, STATUS_NAMES.get(self.status, self.status),
+                                          status_string(self.status)))
 
 
 class Desc(ctypes.Structure):
@@ -150,16 +150,54 @@ def alloc_outputs(desc, device):
     return header, payload, workspace
 
 
+# ---- argument checks before any pointer reaches the library --------------------------------
+# The C functions take no capacities: a tensor that is smaller than the descriptor says, or of
+# another element type, would make a kernel read or write outside it.  Everything is checked
+# here, on the host, and refused with the status code the C header reserves for it.
+INVALID_ARG, BUFFER_TOO_SMALL = 1, 3
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def _check_tensor(t, where, what, dtype_is=None, min_elems=None, min_bytes=None):
+    if t is None:
+        raise AcceptError(INVALID_ARG, "%s: %s is missing" % (where, what))
+    if not t.is_cuda:
+        raise AcceptError(INVALID_ARG, "%s: %s is not a device tensor" % (where, what))
+    if not t.is_contiguous():
+        raise AcceptError(INVALID_ARG, "%s: %s is not contiguous" % (where, what))
+    if dtype_is is not None and dtype_code(t) != dtype_is:
+        raise AcceptError(INVALID_ARG, "%s: %s has dtype %s, the descriptor says %s"
+                          % (where, what, t.dtype, "bfloat16" if dtype_is == BF16 else "float32"))
+    if min_elems is not None and t.numel() < min_elems:
+        raise AcceptError(BUFFER_TOO_SMALL, "%s: %s has %d elements, %d needed" % (where, what, t.numel(), min_elems))
+    if min_bytes is not None and _nbytes(t) < min_bytes:
+        raise AcceptError(BUFFER_TOO_SMALL, "%s: %s has %d bytes, %d needed" % (where, what, _nbytes(t), min_bytes))
+
+
+def _check_compress_args(where, desc, x, alpha_prev, header, payload, workspace, need_alpha):
+    hb, pb = accept_packed_size(desc)  # raises on a bad descriptor
+    _check_tensor(x, where, "x", dtype_is=desc.in_dtype, min_elems=desc.n * desc.m)
+    _check_tensor(header, where, "header", min_bytes=hb)
+    _check_tensor(payload, where, "payload", min_bytes=pb)
+    if workspace is not None:
+        _check_tensor(workspace, where, "workspace", min_bytes=accept_workspace_size(desc))
+    if need_alpha and desc.scheme == MBQ:
+        _check_tensor(alpha_prev, where, "alpha_prev", dtype_is=F32, min_elems=desc.bits)
+
+
 def accept_compress(desc, x, alpha_prev=None, header=None, payload=None, workspace=None):
     """Enqueue compression of the device tensor x on the current stream.
 
     Returns (header, payload) uint8 device tensors (allocated here unless passed in)."""
-    assert x.is_cuda and x.is_contiguous()
     if header is None or payload is None or workspace is None:
         h, p, w = alloc_outputs(desc, x.device)
         header = h if header is None else header
         payload = p if payload is None else payload
         workspace = w if workspace is None else workspace
+    _check_compress_args("accept_compress", desc, x, alpha_prev, header, payload, workspace, True)
     st = lib.accept_compress(ctypes.byref(desc), _ptr(x), _ptr(alpha_prev), _ptr(header), _ptr(payload),
                              _ptr(workspace), _stream_handle())
     _check(st, "accept_compress")
@@ -169,6 +207,7 @@ def accept_compress(desc, x, alpha_prev=None, header=None, payload=None, workspa
 def accept_compress_noalloc(desc, x, alpha_prev, header, payload):
     """accept_compress on the library's built-in scratch: the caller passes every buffer and
     nothing is allocated, here or in the library."""
+    _check_compress_args("accept_compress_noalloc", desc, x, alpha_prev, header, payload, None, True)
     st = lib.accept_compress_noalloc(ctypes.byref(desc), _ptr(x), _ptr(alpha_prev), _ptr(header), _ptr(payload),
                                      _stream_handle())
     _check(st, "accept_compress_noalloc")
@@ -178,9 +217,13 @@ def accept_compress_noalloc(desc, x, alpha_prev, header, payload):
 def accept_decompress(desc, header, payload, out=None):
     """Enqueue decompression on the current stream; returns the flat x_hat device tensor."""
     torch = _torch()
+    hb, pb = accept_packed_size(desc)
+    _check_tensor(header, "accept_decompress", "header", min_bytes=hb)
+    _check_tensor(payload, "accept_decompress", "payload", min_bytes=pb)
     if out is None:
         dt = torch.bfloat16 if desc.out_dtype == BF16 else torch.float32
         out = torch.empty(desc.n * desc.m, dtype=dt, device=payload.device)
+    _check_tensor(out, "accept_decompress", "out", dtype_is=desc.out_dtype, min_elems=desc.n * desc.m)
     st = lib.accept_decompress(ctypes.byref(desc), _ptr(header), _ptr(payload), _ptr(out), _stream_handle())
     _check(st, "accept_decompress")
     return out
@@ -188,10 +231,14 @@ def accept_decompress(desc, header, payload, out=None):
 
 def accept_mbq_init(desc, x, alpha0=None, workspace=None):
     torch = _torch()
+    accept_packed_size(desc)
+    _check_tensor(x, "accept_mbq_init", "x", dtype_is=desc.in_dtype, min_elems=desc.n * desc.m)
     if alpha0 is None:
         alpha0 = torch.empty(desc.bits, dtype=torch.float32, device=x.device)
     if workspace is None:
         workspace = torch.zeros(accept_workspace_size(desc), dtype=torch.uint8, device=x.device)
+    _check_tensor(alpha0, "accept_mbq_init", "alpha0", dtype_is=F32, min_elems=desc.bits)
+    _check_tensor(workspace, "accept_mbq_init", "workspace", min_bytes=accept_workspace_size(desc))
     st = lib.accept_mbq_init(ctypes.byref(desc), _ptr(x), _ptr(alpha0), _ptr(workspace), _stream_handle())
     _check(st, "accept_mbq_init")
     return alpha0
@@ -204,6 +251,7 @@ def accept_mbq_compress_first(desc, x, header=None, payload=None, workspace=None
         header = h if header is None else header
         payload = p if payload is None else payload
         workspace = w if workspace is None else workspace
+    _check_compress_args("accept_mbq_compress_first", desc, x, None, header, payload, workspace, False)
     st = lib.accept_mbq_compress_first(ctypes.byref(desc), _ptr(x), _ptr(header), _ptr(payload), _ptr(workspace),
                                        _stream_handle())
     _check(st, "accept_mbq_compress_first")
@@ -212,6 +260,7 @@ def accept_mbq_compress_first(desc, x, header=None, payload=None, workspace=None
 
 def accept_compress_timed(desc, x, alpha_prev, header, payload, workspace):
     """Measurement variant: returns {stage name: milliseconds}; synchronises."""
+    _check_compress_args("accept_compress_timed", desc, x, alpha_prev, header, payload, workspace, True)
     ms = (ctypes.c_float * MAX_STAGES)()
     ns = ctypes.c_int(0)
     st = lib.accept_compress_timed(ctypes.byref(desc), _ptr(x), _ptr(alpha_prev), _ptr(header), _ptr(payload),
@@ -221,6 +270,10 @@ def accept_compress_timed(desc, x, alpha_prev, header, payload, workspace):
 
 
 def accept_decompress_timed(desc, header, payload, out):
+    hb, pb = accept_packed_size(desc)
+    _check_tensor(header, "accept_decompress_timed", "header", min_bytes=hb)
+    _check_tensor(payload, "accept_decompress_timed", "payload", min_bytes=pb)
+    _check_tensor(out, "accept_decompress_timed", "out", dtype_is=desc.out_dtype, min_elems=desc.n * desc.m)
     ms = (ctypes.c_float * MAX_STAGES)()
     ns = ctypes.c_int(0)
     st = lib.accept_decompress_timed(ctypes.byref(desc), _ptr(header), _ptr(payload), _ptr(out), _stream_handle(),

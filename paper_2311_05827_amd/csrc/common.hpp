@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "accept.h"
+#include "accept_profile.h"
 
 namespace accept {
 
