@@ -139,8 +139,14 @@ __device__ __forceinline__ int build_bucket_table(uint8_t* lut, F count_below) {
   uint32_t* lut32 = reinterpret_cast<uint32_t*>(lut);
   const int lane = threadIdx.x & (kWave - 1);
   int mymax = 0;
+  // Chunk c goes to thread (c * 67) mod 512 of its round: the thresholds sit in a few
+  // neighbouring chunks (values of similar magnitude), and this spreads those chunks over the
+  // wavefronts instead of leaving them all to one.
+  constexpr int NCH = kLutSize / CH;
+  static_assert(NCH == 512, "the chunk permutation below is a bijection on 512 chunks");
 #pragma nounroll
-  for (int b0 = threadIdx.x * CH; b0 < kLutSize; b0 += blockDim.x * CH) {
+  for (int slot = threadIdx.x; slot < NCH; slot += blockDim.x) {
+    const int b0 = ((slot * 67) & (NCH - 1)) * CH;
     const bool neg = b0 >= kLutSize / 2;
     // the chunk's first and last bucket in value order, and the bucket that follows the last
     const int b_first = neg ? b0 + CH - 1 : b0;
