@@ -71,6 +71,29 @@ __device__ __forceinline__ void chan_advance(const ChanGeom& g, ChanPos& p, cons
   if (p.ch >= g.C) p.ch -= g.C;
 }
 
+// How the elements of a 16-byte vector find their range group (the fast paths of the quantizer
+// and of the decoder are compiled once per case):
+constexpr int kOneRange = 0;         // one group for the tensor
+constexpr int kRangePerVector = 1;   // segments are whole vectors: one group per vector, ChanPos.ch its channel
+constexpr int kRangePerElement = 2;  // one element per segment (channels-last) and rows of whole vectors:
+                                     // ChanPos.ch is the vector's place in its row, element e has channel ch*VEC + e
+// The per-group values (reciprocals for the quantizer, scales for the decoder) of a vector's elements.
+template <int MODE, int VEC>
+__device__ __forceinline__ void ranges_of_vector(const float* __restrict__ tab, float one, int32_t ch,
+                                                 float (&out)[VEC]) {
+  if constexpr (MODE == kRangePerElement) {
+#pragma unroll
+    for (int h = 0; h < VEC / 4; ++h) {
+      const float4 t = *reinterpret_cast<const float4*>(tab + int64_t(ch) * VEC + 4 * h);  // tab is 16-byte aligned
+      out[4 * h] = t.x; out[4 * h + 1] = t.y; out[4 * h + 2] = t.z; out[4 * h + 3] = t.w;
+    }
+  } else {
+    const float v = MODE == kRangePerVector ? tab[ch] : one;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) out[e] = v;
+  }
+}
+
 // =========================================================================== range (U1)
 // One range for the tensor: grid-stride 16-byte loads, DPP wave reduction, one partial
 // maximum per workgroup.  max is exact and order independent, so the result is
@@ -207,21 +230,39 @@ __global__ __launch_bounds__(kBlock) void range_columns_kernel(const T* __restri
   }
 }
 
-// Stage 2 and U1b: one wavefront per channel takes the maximum over the channel's seg_len
+// Stage 2 and U1b: one workgroup per channel takes the maximum over the channel's seg_len
 // columns in all nby row blocks, writes s to the header and the reciprocal to the table.
-__global__ __launch_bounds__(kWave) void range_columns_finalize_kernel(const float* __restrict__ colmax, int64_t m,
+// Thread t starts at entry t of the channel's seg_len x nby maxima (row block t / seg_len,
+// column t % seg_len) and steps by 256 entries, carried as (row block, column) so that the
+// loop needs no division.
+__global__ __launch_bounds__(kBlock) void range_columns_finalize_kernel(const float* __restrict__ colmax, int64_t m,
                                                                         int64_t seg_len, int nby, int k,
                                                                         float* __restrict__ header,
                                                                         float* __restrict__ rtab) {
+  __shared__ float red[kBlock / kWave];
   const int64_t ch = blockIdx.x;
+  const float* base = colmax + ch * seg_len;
+  const int64_t dby = int64_t(kBlock) / seg_len, dq = int64_t(kBlock) % seg_len;
+  int64_t by = int64_t(threadIdx.x) / seg_len, q = int64_t(threadIdx.x) % seg_len;
   float c = 0.0f;
-  const int64_t per = seg_len * nby;
-  for (int64_t j = threadIdx.x; j < per; j += kWave) {
-    const int64_t by = j / seg_len;
-    c = fmaxf(c, colmax[by * m + ch * seg_len + (j - by * seg_len)]);
+  while (by < nby) {
+    float v[4];  // four loads in flight
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      v[u] = by < nby ? base[by * m + q] : 0.0f;
+      by += dby;
+      q += dq;
+      if (q >= seg_len) { q -= seg_len; ++by; }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) c = fmaxf(c, v[u]);
   }
   c = wave_max(c);
+  if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = c;
+  __syncthreads();
   if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kBlock / kWave; ++w) c = fmaxf(c, red[w]);
     float s, r;
     scale_from_range(c, k, s, r);
     header[ch] = s;
@@ -276,10 +317,10 @@ __device__ __forceinline__ uint32_t quantize1(float f, float r, uint64_t seed, i
 
 // Four consecutive elements -> one 4k-bit piece, first element most significant.
 template <int K, bool STOCH>
-__device__ __forceinline__ uint32_t quantize4(const float* f, float r, uint64_t seed, int64_t idx0) {
+__device__ __forceinline__ uint32_t quantize4(const float* f, const float* r, uint64_t seed, int64_t idx0) {
   uint32_t piece = 0;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) piece = (piece << K) | quantize1<K, STOCH>(f[e], r, seed, idx0 + e);
+  for (int e = 0; e < 4; ++e) piece = (piece << K) | quantize1<K, STOCH>(f[e], r[e], seed, idx0 + e);
   return piece;
 }
 
@@ -328,7 +369,7 @@ __device__ __forceinline__ void quantize_group8(const T* __restrict__ x, uint8_t
 // elements) and emits k contiguous dwords.  The piece buffer is double buffered so that one
 // barrier per tile is enough.  Per-tensor mode folds U1b into the prologue: every workgroup
 // reduces the range pass's partial maxima itself and workgroup 0 writes s to the header.
-template <typename T, int K, bool PERCH, bool STOCH>
+template <typename T, int K, int MODE, bool STOCH>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     const T* __restrict__ x, uint32_t* __restrict__ payload32, float* __restrict__ header,
     const float* __restrict__ partials, int npart, const float* __restrict__ rtab, int64_t N, int64_t full_tiles,
@@ -342,7 +383,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
 
   const int tid = threadIdx.x;
   float r_tensor = 0.0f;
-  if (!PERCH) {
+  if (MODE == kOneRange) {
     float c = 0.0f;
     for (int i = tid; i < npart; i += kBlock) c = fmaxf(c, partials[i]);
     c = wave_max(c);
@@ -357,7 +398,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
   }
 
   ChanPos tile_pos{0, 0};
-  if (PERCH && full_tiles > 0)
+  if (MODE != kOneRange && full_tiles > 0)
     tile_pos = chan_init(geom, int64_t(blockIdx.x) * (kTileElems / VEC) + tid);
 
   int buf = 0;
@@ -369,17 +410,15 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     ChanPos pos = tile_pos;
 #pragma unroll
     for (int u = 0; u < LOADS; ++u) {
-      float r = r_tensor;
-      if (PERCH) {
-        r = rtab[pos.ch];
-        chan_advance(geom, pos, geom.s256);
-      }
+      float r[VEC];
+      ranges_of_vector<MODE, VEC>(rtab, r_tensor, pos.ch, r);
+      if (MODE != kOneRange) chan_advance(geom, pos, geom.s256);
       const int64_t e0 = tile * kTileElems + int64_t(u * kBlock + tid) * VEC;
 #pragma unroll
       for (int h = 0; h < QPV; ++h)
-        pieces[buf][(u * kBlock + tid) * QPV + h] = quantize4<K, STOCH>(&f[u][4 * h], r, seed, e0 + 4 * h);
+        pieces[buf][(u * kBlock + tid) * QPV + h] = quantize4<K, STOCH>(&f[u][4 * h], &r[4 * h], seed, e0 + 4 * h);
     }
-    if (PERCH) chan_advance(geom, tile_pos, geom.sgrid);
+    if (MODE != kOneRange) chan_advance(geom, tile_pos, geom.sgrid);
     __syncthreads();
     const uint4 a = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid]);
     const uint4 b = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid + 4]);
@@ -394,7 +433,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
   uint8_t* payload8 = reinterpret_cast<uint8_t*>(payload32);
   for (int64_t g = slow_first_group + int64_t(blockIdx.x) * kBlock + tid; g < groups;
        g += int64_t(gridDim.x) * kBlock) {
-    if (PERCH) {
+    if (MODE != kOneRange) {
       quantize_group8<T, K, STOCH>(x, payload8, g, N, payload_bytes, seed,
                                    [&](int64_t i) { return rtab[(i % m) / seg_len]; });
     } else {
@@ -414,7 +453,7 @@ struct CodeWords {
 };
 // e0: element index of the first code (a multiple of 4), relative to a dword-aligned origin.
 template <int K>
-__device__ __forceinline__ void convert_codes4(CodeWords c, int64_t e0, float s, float* out) {
+__device__ __forceinline__ void convert_codes4(CodeWords c, int64_t e0, const float* s, float* out) {
   constexpr int W = 4 * K;
   const int sh = int((e0 * K) & 31);
   const uint64_t win = (uint64_t(__builtin_bswap32(c.hi)) << 32) | __builtin_bswap32(c.lo);
@@ -427,11 +466,12 @@ __device__ __forceinline__ void convert_codes4(CodeWords c, int64_t e0, float s,
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const int q = __builtin_amdgcn_sbfe(int(piece), K * (3 - e), K);
-    out[e] = __fmul_rn(float(q), s);
+    out[e] = __fmul_rn(float(q), s[e]);
   }
 }
 template <int K>
-__device__ __forceinline__ void dequant4(const uint32_t* __restrict__ payload32, int64_t e0, float s, float* out) {
+__device__ __forceinline__ void dequant4(const uint32_t* __restrict__ payload32, int64_t e0, const float* s,
+                                         float* out) {
   const int64_t w0 = (e0 * K) >> 5;
   CodeWords c;
   c.lo = 0;
@@ -462,30 +502,28 @@ __device__ __forceinline__ float dequant1(const uint8_t* __restrict__ payload, i
   return __fmul_rn(float(q), s);
 }
 
-template <typename TO, int K, bool PERCH>
+template <typename TO, int K, int MODE>
 __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(
     const uint32_t* __restrict__ payload32, const float* __restrict__ header, TO* __restrict__ xhat, int64_t N,
     int64_t fast_vecs, int64_t payload_bytes, ChanGeom geom, int64_t m, int64_t seg_len) {
   constexpr int VEC = Elem<TO>::VEC;
   const int64_t stride = int64_t(gridDim.x) * kBlock;
   int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-  const float s_tensor = PERCH ? 0.0f : header[0];
+  const float s_tensor = MODE != kOneRange ? 0.0f : header[0];
   ChanPos pos{0, 0};
-  if (PERCH && v < fast_vecs) pos = chan_init(geom, v);
+  if (MODE != kOneRange && v < fast_vecs) pos = chan_init(geom, v);
   for (; v < fast_vecs; v += stride) {
-    float s = s_tensor;
-    if (PERCH) {
-      s = header[pos.ch];
-      chan_advance(geom, pos, geom.sgrid);
-    }
+    float s[VEC];
+    ranges_of_vector<MODE, VEC>(header, s_tensor, pos.ch, s);
+    if (MODE != kOneRange) chan_advance(geom, pos, geom.sgrid);
     float f[VEC];
 #pragma unroll
-    for (int h = 0; h < VEC / 4; ++h) dequant4<K>(payload32, v * VEC + 4 * h, s, &f[4 * h]);
+    for (int h = 0; h < VEC / 4; ++h) dequant4<K>(payload32, v * VEC + 4 * h, &s[4 * h], &f[4 * h]);
     store_vec(xhat + v * VEC, f);
   }
   const uint8_t* payload8 = reinterpret_cast<const uint8_t*>(payload32);
   for (int64_t i = fast_vecs * VEC + int64_t(blockIdx.x) * kBlock + threadIdx.x; i < N; i += stride) {
-    const float s = PERCH ? header[(i % m) / seg_len] : s_tensor;
+    const float s = MODE != kOneRange ? header[(i % m) / seg_len] : s_tensor;
     store_one(xhat + i, dequant1<K>(payload8, i, payload_bytes, s));
   }
 }
@@ -497,7 +535,7 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_kernel(
 // (Reading the payload straight from global memory gives every lane a 4-byte load of which
 // half is used at k = 4: the small reads, not the stores, held the plain kernel back.)
 // Elements beyond the last whole tile take the scalar path.
-template <typename TO, int K, bool PERCH>
+template <typename TO, int K, int MODE>
 __global__ __launch_bounds__(kBlock) void unpack_dequant_tiled_kernel(
     const uint32_t* __restrict__ payload32, const float* __restrict__ header, TO* __restrict__ xhat, int64_t N,
     int64_t full_tiles, int64_t payload_bytes, ChanGeom geom, int64_t m, int64_t seg_len) {
@@ -507,9 +545,10 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_tiled_kernel(
   constexpr int SWEEPS = (TILE_DW + 4 * kBlock - 1) / (4 * kBlock);
   __shared__ __attribute__((aligned(16))) uint32_t tile[2][TILE_DW + 4];  // + one dword a straddling pair may touch
   const int tid = threadIdx.x;
-  const float s_tensor = PERCH ? 0.0f : header[0];
+  const float s_tensor = MODE != kOneRange ? 0.0f : header[0];
   ChanPos tile_pos{0, 0};
-  if (PERCH && full_tiles > 0) tile_pos = chan_init(geom, int64_t(blockIdx.x) * (kTileElems / VEC) + tid);
+  if (MODE != kOneRange && full_tiles > 0)
+    tile_pos = chan_init(geom, int64_t(blockIdx.x) * (kTileElems / VEC) + tid);
   if (tid < 4) { tile[0][TILE_DW + tid] = 0u; tile[1][TILE_DW + tid] = 0u; }
   int buf = 0;
   for (int64_t t = blockIdx.x; t < full_tiles; t += gridDim.x, buf ^= 1) {
@@ -525,11 +564,9 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_tiled_kernel(
     ChanPos pos = tile_pos;
 #pragma unroll
     for (int j = 0; j < VPT; ++j) {
-      float s = s_tensor;
-      if (PERCH) {
-        s = header[pos.ch];
-        chan_advance(geom, pos, geom.s256);
-      }
+      float s[VEC];
+      ranges_of_vector<MODE, VEC>(header, s_tensor, pos.ch, s);
+      if (MODE != kOneRange) chan_advance(geom, pos, geom.s256);
       const int vec_in_tile = j * kBlock + tid;
       float f[VEC];
 #pragma unroll
@@ -539,16 +576,16 @@ __global__ __launch_bounds__(kBlock) void unpack_dequant_tiled_kernel(
         CodeWords c;
         c.hi = tile[buf][bit >> 5];
         c.lo = (32 % (4 * K) != 0) ? tile[buf][(bit >> 5) + 1] : 0u;
-        convert_codes4<K>(c, e0, s, &f[4 * h]);
+        convert_codes4<K>(c, e0, &s[4 * h], &f[4 * h]);
       }
       store_vec(xhat + (t * (kTileElems / VEC) + vec_in_tile) * VEC, f);
     }
-    if (PERCH) chan_advance(geom, tile_pos, geom.sgrid);
+    if (MODE != kOneRange) chan_advance(geom, tile_pos, geom.sgrid);
   }
   const uint8_t* payload8 = reinterpret_cast<const uint8_t*>(payload32);
   const int64_t stride = int64_t(gridDim.x) * kBlock;
   for (int64_t i = full_tiles * kTileElems + int64_t(blockIdx.x) * kBlock + tid; i < N; i += stride) {
-    const float s = PERCH ? header[(i % m) / seg_len] : s_tensor;
+    const float s = MODE != kOneRange ? header[(i % m) / seg_len] : s_tensor;
     store_one(xhat + i, dequant1<K>(payload8, i, payload_bytes, s));
   }
 }
@@ -561,7 +598,7 @@ ChanStep make_step(int64_t step_vecs, int64_t seg_vecs, int64_t C) {
   return st;
 }
 
-template <typename T, int K, bool PERCH, bool STOCH>
+template <typename T, int K, int MODE, bool STOCH>
 hipError_t launch_quant(const accept_desc& d, const UPlan& p, const T* x, float* header, uint32_t* payload,
                         const float* partials, const float* rtab, hipStream_t s) {
   const int64_t N = p.N;
@@ -575,14 +612,15 @@ hipError_t launch_quant(const accept_desc& d, const UPlan& p, const T* x, float*
   ChanGeom g{};
   g.seg_vecs = 1;
   g.C = 1;
-  if (PERCH && p.fast) {
-    g.seg_vecs = p.seg_len / p.vec;
-    g.C = int32_t(p.C);
-    g.s256 = make_step(kBlock, g.seg_vecs, p.C);
-    g.sgrid = make_step(int64_t(grid) * (kTileElems / p.vec), g.seg_vecs, p.C);
+  if (MODE != kOneRange && p.fast) {
+    // per element: the "segments" are single vectors and the "channels" the m / vec vectors of a row
+    g.seg_vecs = MODE == kRangePerElement ? 1 : p.seg_len / p.vec;
+    g.C = int32_t(MODE == kRangePerElement ? p.m / p.vec : p.C);
+    g.s256 = make_step(kBlock, g.seg_vecs, g.C);
+    g.sgrid = make_step(int64_t(grid) * (kTileElems / p.vec), g.seg_vecs, g.C);
   }
   const int64_t payload_bytes = (N * K + 7) / 8;
-  hipLaunchKernelGGL((quantize_pack_kernel<T, K, PERCH, STOCH>), dim3(grid), dim3(kBlock), 0, s, x, payload, header,
+  hipLaunchKernelGGL((quantize_pack_kernel<T, K, MODE, STOCH>), dim3(grid), dim3(kBlock), 0, s, x, payload, header,
                      partials, p.range_grid, rtab, N, full_tiles, slow_first, payload_bytes, g, p.m, p.seg_len,
                      d.seed);
   return hipGetLastError();
@@ -768,14 +806,17 @@ int plain_grid(int64_t units) {
 template <typename T, int K>
 hipError_t launch_quant_k(const accept_desc& d, const UPlan& p, const T* x, float* header, uint32_t* payload,
                           const float* partials, const float* rtab, hipStream_t s) {
-  const bool perch = p.mode != U_TENSOR;
   const bool stoch = d.rounding == ACCEPT_ROUND_STOCHASTIC;
-  if (perch) {
-    return stoch ? launch_quant<T, K, true, true>(d, p, x, header, payload, partials, rtab, s)
-                 : launch_quant<T, K, true, false>(d, p, x, header, payload, partials, rtab, s);
+  if (p.mode == U_TENSOR) {
+    return stoch ? launch_quant<T, K, kOneRange, true>(d, p, x, header, payload, partials, rtab, s)
+                 : launch_quant<T, K, kOneRange, false>(d, p, x, header, payload, partials, rtab, s);
   }
-  return stoch ? launch_quant<T, K, false, true>(d, p, x, header, payload, partials, rtab, s)
-               : launch_quant<T, K, false, false>(d, p, x, header, payload, partials, rtab, s);
+  if (p.per_element) {
+    return stoch ? launch_quant<T, K, kRangePerElement, true>(d, p, x, header, payload, partials, rtab, s)
+                 : launch_quant<T, K, kRangePerElement, false>(d, p, x, header, payload, partials, rtab, s);
+  }
+  return stoch ? launch_quant<T, K, kRangePerVector, true>(d, p, x, header, payload, partials, rtab, s)
+               : launch_quant<T, K, kRangePerVector, false>(d, p, x, header, payload, partials, rtab, s);
 }
 
 template <typename T>
@@ -804,7 +845,7 @@ hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, floa
   mark(tm, s);
   const bool plain = d.layout != ACCEPT_LAYOUT_PACKED;
   if (p.mode == U_GENERIC) {
-    hipLaunchKernelGGL(range_columns_finalize_kernel, dim3(unsigned(p.C)), dim3(kWave), 0, s, partials, p.m, p.seg_len,
+    hipLaunchKernelGGL(range_columns_finalize_kernel, dim3(unsigned(p.C)), dim3(kBlock), 0, s, partials, p.m, p.seg_len,
                        p.col_grid_y, d.bits, header, rtab);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -851,7 +892,7 @@ hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, floa
   return hipSuccess;
 }
 
-template <typename TO, int K, bool PERCH>
+template <typename TO, int K, int MODE>
 hipError_t launch_dequant(const accept_desc& d, const float* header, const uint32_t* payload, TO* xhat,
                           hipStream_t s) {
   constexpr int VEC = Elem<TO>::VEC;
@@ -860,7 +901,7 @@ hipError_t launch_dequant(const accept_desc& d, const float* header, const uint3
   const int64_t seg_len = d.m / C;
   // The vector path covers whole groups of 32 elements (k whole dwords), so that no dword
   // load reaches past the payload; per channel it also needs vectors that stay in a segment.
-  const bool fast = !PERCH || (seg_len % VEC == 0);
+  const bool fast = MODE != kRangePerVector || (seg_len % VEC == 0);
   // widths whose 4-code fields straddle dwords read dword pairs: keep one group in reserve
   const int64_t groups32 = (32 % (4 * K) != 0) ? (N / 32 > 0 ? N / 32 - 1 : 0) : N / 32;
   const int64_t fast_vecs = fast ? groups32 * (32 / VEC) : 0;
@@ -871,10 +912,10 @@ hipError_t launch_dequant(const accept_desc& d, const float* header, const uint3
   ChanGeom g{};
   g.seg_vecs = 1;
   g.C = 1;
-  if (PERCH && fast) {
-    g.seg_vecs = seg_len / VEC;
-    g.C = int32_t(C);
-    g.sgrid = make_step(int64_t(grid) * kBlock, g.seg_vecs, C);
+  if (MODE != kOneRange && fast) {
+    g.seg_vecs = MODE == kRangePerElement ? 1 : seg_len / VEC;
+    g.C = int32_t(MODE == kRangePerElement ? d.m / VEC : C);
+    g.sgrid = make_step(int64_t(grid) * kBlock, g.seg_vecs, g.C);
     g.s256 = g.sgrid;
   }
   const int64_t payload_bytes = (N * K + 7) / 8;
@@ -883,15 +924,15 @@ hipError_t launch_dequant(const accept_desc& d, const float* header, const uint3
     const int64_t tail = N - full_tiles * kTileElems;
     int64_t want = full_tiles > (tail + kBlock - 1) / kBlock ? full_tiles : (tail + kBlock - 1) / kBlock;
     const int tgrid = int(want < kDequantGridMax ? want : kDequantGridMax);
-    if (PERCH) {
-      g.s256 = make_step(kBlock, g.seg_vecs, C);
-      g.sgrid = make_step(int64_t(tgrid) * (kTileElems / VEC), g.seg_vecs, C);
+    if (MODE != kOneRange) {
+      g.s256 = make_step(kBlock, g.seg_vecs, g.C);
+      g.sgrid = make_step(int64_t(tgrid) * (kTileElems / VEC), g.seg_vecs, g.C);
     }
-    hipLaunchKernelGGL((unpack_dequant_tiled_kernel<TO, K, PERCH>), dim3(tgrid), dim3(kBlock), 0, s, payload, header,
+    hipLaunchKernelGGL((unpack_dequant_tiled_kernel<TO, K, MODE>), dim3(tgrid), dim3(kBlock), 0, s, payload, header,
                        xhat, N, full_tiles, payload_bytes, g, d.m, seg_len);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL((unpack_dequant_kernel<TO, K, PERCH>), dim3(grid), dim3(kBlock), 0, s, payload, header, xhat, N,
+  hipLaunchKernelGGL((unpack_dequant_kernel<TO, K, MODE>), dim3(grid), dim3(kBlock), 0, s, payload, header, xhat, N,
                      fast_vecs, payload_bytes, g, d.m, seg_len);
   return hipGetLastError();
 }
@@ -914,11 +955,16 @@ hipError_t decompress_typed(const accept_desc& d, const float* header, const uin
     }
     return hipGetLastError();
   }
-  const bool perch = d.channels > 1;
-#define ACCEPT_DQ(KK)                                                              \
-  case KK:                                                                         \
-    return perch ? launch_dequant<TO, KK, true>(d, header, payload, xhat, s)       \
-                 : launch_dequant<TO, KK, false>(d, header, payload, xhat, s);
+  // channels-last (every element of a row its own channel) with rows of whole vectors: one range per element
+  // (the scales are then read as 16-byte vectors: a header that is only 4-byte aligned takes the plain path)
+  const bool per_element = d.channels > 1 && d.channels == d.m && d.m % Elem<TO>::VEC == 0 &&
+                           (reinterpret_cast<uintptr_t>(header) & 15u) == 0;
+  const int mode = d.channels > 1 ? (per_element ? kRangePerElement : kRangePerVector) : kOneRange;
+#define ACCEPT_DQ(KK)                                                                                   \
+  case KK:                                                                                              \
+    return mode == kRangePerElement  ? launch_dequant<TO, KK, kRangePerElement>(d, header, payload, xhat, s) \
+           : mode == kRangePerVector ? launch_dequant<TO, KK, kRangePerVector>(d, header, payload, xhat, s)  \
+                                     : launch_dequant<TO, KK, kOneRange>(d, header, payload, xhat, s);
   switch (d.bits) {
     ACCEPT_DQ(2) ACCEPT_DQ(3) ACCEPT_DQ(4) ACCEPT_DQ(5) ACCEPT_DQ(6) ACCEPT_DQ(7) ACCEPT_DQ(8)
     default: return hipErrorInvalidValue;
@@ -959,7 +1005,10 @@ UPlan make_uplan(const accept_desc& d) {
     partial_bytes = size_t(p.items) * sizeof(float);
   } else {
     p.mode = U_GENERIC;
-    p.fast = (p.seg_len % p.vec == 0);
+    // channels-last (one element per segment) with rows of whole vectors: the quantizer's fast
+    // path with one range per element
+    p.per_element = p.seg_len == 1 && d.m % p.vec == 0;
+    p.fast = (p.seg_len % p.vec == 0) || p.per_element;
     // column pass: threads own vectors of columns when every row keeps them aligned, else columns
     const int64_t ncv = (d.m % p.vec == 0) ? d.m / p.vec : d.m;
     int tx = 1;

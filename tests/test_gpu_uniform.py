@@ -150,6 +150,40 @@ def test_per_channel_generic_geometries(A, k):
     run_case(A, x, k, 37, 3900, channels=1300, tag="seg3 wide")
 
 
+@pytest.mark.parametrize("k", KS)
+def test_channels_last_one_range_per_element(A, k):
+    """Rows of C channels with one element each and a gain per channel spanning six decades: whole
+    tiles (vector path, every element of a vector its own range) plus a ragged tail, float32 and
+    bfloat16, nearest-even and stochastic; row lengths that no 16-byte vector divides take the plain path."""
+    for rows, C in [(700, 64), (301, 136), (1237, 40), (530, 36), (2100, 8)]:
+        x = si.make_shape("grad", (rows, C), 70 + k)
+        gain = np.float32(10.0) ** np.linspace(-3, 3, C, dtype=np.float32)
+        x = np.ascontiguousarray(x * gain[None, :], dtype=np.float32)
+        run_case(A, x, k, rows, C, channels=C, tag="channels-last %d" % C)
+        run_case(A, x, k, rows, C, channels=C, in_bf16=True, out_bf16=True, tag="channels-last %d bf16" % C)
+    run_case(A, x, k, rows, C, channels=C, rounding=1, seed=77, tag="channels-last stochastic")
+
+
+def test_channels_last_decoder_with_unaligned_header(A):
+    """A header that is only 4-byte aligned (the contract's minimum) decodes to the same values."""
+    torch = torch_mod()
+    rows, C, k = 900, 64, 5
+    x = si.make_shape("grad", (rows, C), 91) * (np.arange(1, C + 1, dtype=np.float32)[None, :])
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    xd, _ = to_dev(x)
+    d = A.make_desc(A.UNIFORM, k, rows, C, channels=C)
+    header, payload = A.accept_compress(d, xd)
+    ref = A.accept_decompress(d, header, payload)
+    shifted = torch.empty(header.numel() + 4, dtype=torch.uint8, device=header.device)
+    shifted[4:] = header
+    got = A.accept_decompress(d, shifted[4:], payload)
+    torch.cuda.synchronize()
+    assert shifted[4:].data_ptr() % 16 == 4
+    oh, op = orc.uniform_compress(x, k, rows, C, C)
+    assert out_to_numpy(got).tobytes() == orc.uniform_decompress(oh, op, k, rows, C, C).tobytes()
+    assert out_to_numpy(ref).tobytes() == out_to_numpy(got).tobytes()
+
+
 @pytest.mark.parametrize("k", [2, 4, 7, 8])
 def test_stochastic_rounding_bit_exact(A, k):
     x = si.make_shape("grad_outliers", (2, 8192 + 100), 60 + k)
