@@ -14,11 +14,12 @@ namespace accept {
 
 namespace {
 
-// The range pass reads with streaming loads as well: measured best in a mix of calls (cacheable
-// loads make the quantize pass a little faster and the range pass, and the mix, slower).
+// The range pass reads with ordinary (cacheable) loads: the quantize pass reads the same tensor
+// again right after it, last-read data first, and finds a good part of it still in the memory-side
+// cache and the end of it in L2 (streaming loads would leave neither).
 template <typename T, int V>
 __device__ __forceinline__ void load_range(const T* p, float (&f)[V]) {
-  load_vec_stream(p, f);
+  widen(load16(p), f);
 }
 
 constexpr float kTinyRange = 0x1p-100f;     // smaller ranges count as an all-zero tensor
@@ -26,6 +27,7 @@ constexpr float kRoundMagic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to i
 constexpr int kRangeGridMax = 512;     // partial maxima of the per-tensor range pass
 constexpr int kQuantGridMax = 2048;    // workgroups of the quantize+pack kernel
 constexpr int kDequantGridMax = 8192;
+static_assert(kQuantGridMax % 8 == 0 && kRangeGridMax % 8 == 0, "grids at their caps keep tile and workgroup index equal modulo 8");
 static_assert(kRangeGridMax <= 4096, "the workspace holds at most 4096 partial maxima");
 
 // s = c / L and r = L / c as correctly rounded float32 quotients (a float64 quotient of two
@@ -71,6 +73,14 @@ __device__ __forceinline__ void chan_advance(const ChanGeom& g, ChanPos& p, cons
   if (p.ch >= g.C) p.ch -= g.C;
 }
 
+__device__ __forceinline__ void chan_retreat(const ChanGeom& g, ChanPos& p, const ChanStep& st) {
+  p.rem -= st.dr;
+  int32_t borrow = 0;
+  if (p.rem < 0) { p.rem += g.seg_vecs; borrow = 1; }
+  p.ch -= st.dch + borrow;
+  if (p.ch < 0) p.ch += g.C;
+}
+
 // How the elements of a 16-byte vector find their range group (the fast paths of the quantizer
 // and of the decoder are compiled once per case):
 constexpr int kOneRange = 0;         // one group for the tensor
@@ -95,29 +105,34 @@ __device__ __forceinline__ void ranges_of_vector(const float* __restrict__ tab, 
 }
 
 // =========================================================================== range (U1)
-// One range for the tensor: grid-stride 16-byte loads, DPP wave reduction, one partial
-// maximum per workgroup.  max is exact and order independent, so the result is
-// reproducible without atomics or a fixed order.
+// One range for the tensor: workgroup b reads the tiles b, b + grid, ... (the quantize pass's
+// tiles, 8192 consecutive elements, all of a thread's 16-byte loads of a tile in flight together),
+// DPP wave reduction, one partial maximum per workgroup.  max is exact and order independent, so
+// the result is reproducible without atomics or a fixed order.  Tile t is read by a workgroup whose
+// index is t modulo 8 (grids of more than 8 workgroups are multiples of 8): under round-robin
+// dispatch that is also the die whose L2 the quantize pass reads tile t through.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void range_tensor_kernel(const T* __restrict__ x, int64_t N,
                                                                float* __restrict__ partials) {
   constexpr int VEC = Elem<T>::VEC;
-  constexpr int UNROLL = 4;
+  constexpr int LOADS = kTileElems / (kBlock * VEC);  // vectors per thread per tile
   __shared__ float red[kBlock / kWave];
   const int64_t nvec = N / VEC;
-  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  const int64_t full_tiles = N / kTileElems;
   float c = 0.0f;
-  int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-  for (; v + (UNROLL - 1) * stride < nvec; v += UNROLL * stride) {
-    float f[UNROLL][VEC];
+  for (int64_t tile = blockIdx.x; tile < full_tiles; tile += gridDim.x) {
+    const T* xt = x + tile * kTileElems;
+    float f[LOADS][VEC];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) load_range<T, VEC>(x + (v + u * stride) * VEC, f[u]);
+    for (int u = 0; u < LOADS; ++u) load_range<T, VEC>(xt + (u * kBlock + threadIdx.x) * VEC, f[u]);
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u)
+    for (int u = 0; u < LOADS; ++u)
 #pragma unroll
       for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[u][e]));
   }
-  for (; v < nvec; v += stride) {
+  const int64_t stride = int64_t(gridDim.x) * kBlock;
+  for (int64_t v = full_tiles * (kTileElems / VEC) + int64_t(blockIdx.x) * kBlock + threadIdx.x; v < nvec;
+       v += stride) {
     float f[VEC];
     load_range<T, VEC>(x + v * VEC, f);
 #pragma unroll
@@ -137,16 +152,28 @@ __global__ __launch_bounds__(kBlock) void range_tensor_kernel(const T* __restric
 }
 
 // One range per channel, long segments: one wavefront reduces one chunk of one segment
-// (segment = channel ch of batch row r, contiguous in memory); partial index =
-// (r*C + ch)*cps + chunk.
+// (segment = channel ch of batch row r, contiguous in memory; chunks are at most a tile long);
+// partial index = (r*C + ch)*cps + chunk.  Workgroup t takes the chunks that begin inside tile t
+// of the quantize pass (8192 consecutive elements), its wavefronts in turn: the data a die reads
+// here is, up to a chunk's overhang, the data the quantize pass reads through the same die's L2.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restrict__ x, int64_t items, int64_t cps,
                                                                  int64_t seg_vecs, int64_t chunk_vecs,
                                                                  float* __restrict__ partials) {
   constexpr int VEC = Elem<T>::VEC;
+  constexpr int64_t TILE_VECS = kTileElems / VEC;
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t waves = int64_t(gridDim.x) * (kBlock / kWave);
-  for (int64_t it = int64_t(blockIdx.x) * (kBlock / kWave) + threadIdx.x / kWave; it < items; it += waves) {
+  // first chunk that begins at or after vector a: the segment of a, and the chunk of a rounded up
+  auto first_item_from = [&](int64_t a) {
+    int64_t sid = a / seg_vecs;
+    int64_t chunk = (a - sid * seg_vecs + chunk_vecs - 1) / chunk_vecs;
+    if (chunk >= cps) { sid += 1; chunk = 0; }
+    const int64_t it = sid * cps + chunk;
+    return it < items ? it : items;
+  };
+  const int64_t it_lo = first_item_from(int64_t(blockIdx.x) * TILE_VECS);
+  const int64_t it_hi = blockIdx.x + 1 == gridDim.x ? items : first_item_from((int64_t(blockIdx.x) + 1) * TILE_VECS);
+  for (int64_t it = it_lo + threadIdx.x / kWave; it < it_hi; it += kBlock / kWave) {
     const int64_t sid = it / cps;
     const int64_t chunk = it - sid * cps;
     const int64_t first = chunk * chunk_vecs;
@@ -373,7 +400,8 @@ template <typename T, int K, int MODE, bool STOCH>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     const T* __restrict__ x, uint32_t* __restrict__ payload32, float* __restrict__ header,
     const float* __restrict__ partials, int npart, const float* __restrict__ rtab, int64_t N, int64_t full_tiles,
-    int64_t slow_first_group, int64_t payload_bytes, ChanGeom geom, int64_t m, int64_t seg_len, uint64_t seed) {
+    int64_t rev_tiles, int64_t slow_first_group, int64_t payload_bytes, ChanGeom geom, int64_t m, int64_t seg_len,
+    uint64_t seed) {
   constexpr int VEC = Elem<T>::VEC;
   constexpr int QPV = VEC / 4;                       // pieces per vector
   constexpr int LOADS = kTileElems / (kBlock * VEC);  // vectors per thread per tile
@@ -397,12 +425,20 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     if (blockIdx.x == 0 && tid == 0) header[0] = s;
   }
 
+  // Tile order.  The range pass has just read the tensor front to back, so its end is what the
+  // caches still hold: the first rev_tiles tiles (a multiple of 8, as is the grid then) are taken
+  // last to first in groups of eight, tile = rev_tiles - 8 - 8*(i / 8) + i % 8 for the i-th tile
+  // of the plain order.  A workgroup's tiles then step backwards by one grid stride, and tile and
+  // workgroup index stay equal modulo 8: the die that read a tile in the range pass reads it
+  // again here.  The up to seven tiles after rev_tiles keep their plain places.
   ChanPos tile_pos{0, 0};
-  if (MODE != kOneRange && full_tiles > 0)
-    tile_pos = chan_init(geom, int64_t(blockIdx.x) * (kTileElems / VEC) + tid);
-
   int buf = 0;
-  for (int64_t tile = blockIdx.x; tile < full_tiles; tile += gridDim.x, buf ^= 1) {
+  for (int64_t tile_f = blockIdx.x; tile_f < full_tiles; tile_f += gridDim.x, buf ^= 1) {
+    const bool reversed = tile_f < rev_tiles;
+    const int64_t tile = reversed ? rev_tiles - 8 - (tile_f & ~int64_t(7)) + (tile_f & 7) : tile_f;
+    // the workgroup's first tile, and its one tile (if any) beyond the reversed part
+    if (MODE != kOneRange && (tile_f == int64_t(blockIdx.x) || !reversed))
+      tile_pos = chan_init(geom, tile * (kTileElems / VEC) + tid);
     const T* xt = x + tile * kTileElems;
     float f[LOADS][VEC];
 #pragma unroll
@@ -418,7 +454,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
       for (int h = 0; h < QPV; ++h)
         pieces[buf][(u * kBlock + tid) * QPV + h] = quantize4<K, STOCH>(&f[u][4 * h], &r[4 * h], seed, e0 + 4 * h);
     }
-    if (MODE != kOneRange) chan_advance(geom, tile_pos, geom.sgrid);
+    if (MODE != kOneRange) chan_retreat(geom, tile_pos, geom.sgrid);
     __syncthreads();
     const uint4 a = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid]);
     const uint4 b = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid + 4]);
@@ -609,6 +645,8 @@ hipError_t launch_quant(const accept_desc& d, const UPlan& p, const T* x, float*
   int64_t want = full_tiles > (slow_groups + kBlock - 1) / kBlock ? full_tiles : (slow_groups + kBlock - 1) / kBlock;
   if (want < 1) want = 1;
   const int grid = int(want < kQuantGridMax ? want : kQuantGridMax);
+  // the reversed tile order needs tile and workgroup index to agree modulo 8
+  const int64_t rev_tiles = (grid % 8 == 0) ? (full_tiles & ~int64_t(7)) : 0;
   ChanGeom g{};
   g.seg_vecs = 1;
   g.C = 1;
@@ -621,8 +659,8 @@ hipError_t launch_quant(const accept_desc& d, const UPlan& p, const T* x, float*
   }
   const int64_t payload_bytes = (N * K + 7) / 8;
   hipLaunchKernelGGL((quantize_pack_kernel<T, K, MODE, STOCH>), dim3(grid), dim3(kBlock), 0, s, x, payload, header,
-                     partials, p.range_grid, rtab, N, full_tiles, slow_first, payload_bytes, g, p.m, p.seg_len,
-                     d.seed);
+                     partials, p.range_grid, rtab, N, full_tiles, rev_tiles, slow_first, payload_bytes, g, p.m,
+                     p.seg_len, d.seed);
   return hipGetLastError();
 }
 
@@ -828,9 +866,8 @@ hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, floa
   if (p.mode == U_TENSOR) {
     hipLaunchKernelGGL((range_tensor_kernel<T>), dim3(p.range_grid), dim3(kBlock), 0, s, x, p.N, partials);
   } else if (p.mode == U_SEGMENTED) {
-    const int64_t blocks = (p.items + (kBlock / kWave) - 1) / (kBlock / kWave);
-    const int grid = int(blocks < 65536 ? blocks : 65536);
-    hipLaunchKernelGGL((range_segments_kernel<T>), dim3(grid), dim3(kBlock), 0, s, x, p.items, p.cps,
+    const int64_t tiles = (p.N + kTileElems - 1) / kTileElems;  // below 2^31: N is at most 2^40
+    hipLaunchKernelGGL((range_segments_kernel<T>), dim3(unsigned(tiles)), dim3(kBlock), 0, s, x, p.items, p.cps,
                        p.seg_len / p.vec, p.chunk_vecs, partials);
   } else {
     const dim3 grid(unsigned(p.col_grid_x), unsigned(p.col_grid_y));
@@ -989,8 +1026,7 @@ UPlan make_uplan(const accept_desc& d) {
   if (p.C == 1) {
     p.mode = U_TENSOR;
     p.fast = true;
-    const int64_t nvec = p.N / p.vec;
-    int64_t blocks = (nvec + int64_t(kBlock) * 4 - 1) / (int64_t(kBlock) * 4);
+    int64_t blocks = p.N / kTileElems;  // one tile per workgroup and round
     if (blocks < 1) blocks = 1;
     p.range_grid = int(blocks < kRangeGridMax ? blocks : kRangeGridMax);
     partial_bytes = size_t(4096) * sizeof(float);
@@ -998,7 +1034,7 @@ UPlan make_uplan(const accept_desc& d) {
     p.mode = U_SEGMENTED;
     p.fast = true;
     const int64_t seg_vecs = p.seg_len / p.vec;
-    const int64_t max_chunk = 4096;  // vectors (64 KiB) one wavefront reduces
+    const int64_t max_chunk = kTileElems / p.vec;  // vectors one wavefront reduces: at most a tile of the quantize pass
     p.cps = (seg_vecs + max_chunk - 1) / max_chunk;
     p.chunk_vecs = (seg_vecs + p.cps - 1) / p.cps;
     p.items = d.n * p.C * p.cps;
