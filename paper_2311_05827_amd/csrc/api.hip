@@ -245,7 +245,7 @@ const char* accept_stage_name(const accept_desc* desc, int is_decompress, int i)
     static const char* const names[] = {"range", "range_finalize", "quantize_plain"};
     return i < 3 ? names[i] : nullptr;
   }
-  if (desc->channels > 1) {
+  if (desc->channels > 1 && !make_uplan(*desc).local_ranges) {
     static const char* const names[] = {"range", "range_finalize", "quantize_pack"};
     return i < 3 ? names[i] : nullptr;
   }

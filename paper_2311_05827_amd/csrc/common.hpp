@@ -66,6 +66,7 @@ struct UPlan {
   int64_t col_grid_x;  // U_GENERIC: workgroups across the columns
   int col_grid_y;      // U_GENERIC: row blocks = maxima kept per column
   bool fast;           // vector path usable (every 16-byte vector lies inside one range group, or per_element)
+  bool local_ranges;   // U_SEGMENTED: the quantize pass finishes the per-channel ranges itself, tile by tile
   bool per_element;    // U_GENERIC: one element per segment and rows of whole vectors (channels-last)
   size_t off_rtab;     // byte offset of the per-channel reciprocal table in the workspace
   size_t bytes;        // workspace bytes

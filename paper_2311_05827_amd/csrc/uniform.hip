@@ -30,13 +30,13 @@ constexpr int kDequantGridMax = 8192;
 static_assert(kQuantGridMax % 8 == 0 && kRangeGridMax % 8 == 0, "grids at their caps keep tile and workgroup index equal modulo 8");
 static_assert(kRangeGridMax <= 4096, "the workspace holds at most 4096 partial maxima");
 
-// s = c / L and r = L / c as correctly rounded float32 quotients (a float64 quotient of two
-// float32 values rounds to the same float32 as the exact quotient).
+// s = c / L and r = L / c as correctly rounded float32 quotients (L is a small integer, exact in
+// float32; __fdiv_rn is the IEEE round-to-nearest-even division).
 __device__ __forceinline__ void scale_from_range(float c, int k, float& s, float& r) {
-  const double L = double((1 << (k - 1)) - 1);
+  const float L = float((1 << (k - 1)) - 1);
   if (c >= kTinyRange) {
-    s = float(double(c) / L);
-    r = float(L / double(c));
+    s = __fdiv_rn(c, L);
+    r = __fdiv_rn(L, c);
   } else {
     s = 0.0f;
     r = 0.0f;
@@ -73,6 +73,16 @@ __device__ __forceinline__ void chan_advance(const ChanGeom& g, ChanPos& p, cons
   if (p.ch >= g.C) p.ch -= g.C;
 }
 
+// kRangePerVectorLocal: the range pass left `per` partial maxima for every channel, those of
+// channel ch at partials[ch * per ..].
+struct LocalRanges {
+  int32_t per;
+};
+// Used for segments of at least 2048 elements; a tile is 8192 elements: it touches at most
+// 8192/2048 + 1 segments.
+constexpr int kLocalRanges = 8;
+constexpr int kLocalMinSegment = 2048;
+static_assert(kTileElems / kLocalMinSegment + 1 <= kLocalRanges, "entries of a tile's table");
 __device__ __forceinline__ void chan_retreat(const ChanGeom& g, ChanPos& p, const ChanStep& st) {
   p.rem -= st.dr;
   int32_t borrow = 0;
@@ -87,6 +97,9 @@ constexpr int kOneRange = 0;         // one group for the tensor
 constexpr int kRangePerVector = 1;   // segments are whole vectors: one group per vector, ChanPos.ch its channel
 constexpr int kRangePerElement = 2;  // one element per segment (channels-last) and rows of whole vectors:
                                      // ChanPos.ch is the vector's place in its row, element e has channel ch*VEC + e
+constexpr int kRangePerVectorLocal = 3;  // as kRangePerVector, quantizer only: no table in memory yet, the workgroup
+                                         // finishes the ranges of each tile's channels itself; ChanPos.ch then indexes
+                                         // its own small table (channel minus the tile's first channel, modulo C)
 // The per-group values (reciprocals for the quantizer, scales for the decoder) of a vector's elements.
 template <int MODE, int VEC>
 __device__ __forceinline__ void ranges_of_vector(const float* __restrict__ tab, float one, int32_t ch,
@@ -98,7 +111,7 @@ __device__ __forceinline__ void ranges_of_vector(const float* __restrict__ tab, 
       out[4 * h] = t.x; out[4 * h + 1] = t.y; out[4 * h + 2] = t.z; out[4 * h + 3] = t.w;
     }
   } else {
-    const float v = MODE == kRangePerVector ? tab[ch] : one;
+    const float v = MODE == kOneRange ? one : tab[ch];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) out[e] = v;
   }
@@ -153,13 +166,13 @@ __global__ __launch_bounds__(kBlock) void range_tensor_kernel(const T* __restric
 
 // One range per channel, long segments: one wavefront reduces one chunk of one segment
 // (segment = channel ch of batch row r, contiguous in memory; chunks are at most a tile long);
-// partial index = (r*C + ch)*cps + chunk.  Workgroup t takes the chunks that begin inside tile t
+// partial index = (ch*cps + chunk)*rows + r: the maxima of one channel lie together.  Workgroup t takes the chunks that begin inside tile t
 // of the quantize pass (8192 consecutive elements), its wavefronts in turn: the data a die reads
 // here is, up to a chunk's overhang, the data the quantize pass reads through the same die's L2.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restrict__ x, int64_t items, int64_t cps,
-                                                                 int64_t seg_vecs, int64_t chunk_vecs,
-                                                                 float* __restrict__ partials) {
+                                                                 int64_t seg_vecs, int64_t chunk_vecs, int64_t rows,
+                                                                 int64_t C, float* __restrict__ partials) {
   constexpr int VEC = Elem<T>::VEC;
   constexpr int64_t TILE_VECS = kTileElems / VEC;
   const int lane = threadIdx.x & (kWave - 1);
@@ -198,7 +211,8 @@ __global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restr
       for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[e]));
     }
     c = wave_max(c);  // every lane of the wavefront reaches this point: the loop bounds are wave-uniform
-    if (lane == 0) partials[it] = c;
+    const int64_t row = sid / C;
+    if (lane == 0) partials[((sid - row * C) * cps + chunk) * rows + row] = c;
   }
 }
 
@@ -297,19 +311,14 @@ __global__ __launch_bounds__(kBlock) void range_columns_finalize_kernel(const fl
   }
 }
 
-// U1b per channel: reduce the channel's partial maxima, write s to the header and the
-// reciprocal r to the workspace table.  One wavefront per channel.
-__global__ __launch_bounds__(kWave) void range_finalize_kernel(const float* __restrict__ partials, int64_t n_rows,
-                                                                int64_t C, int64_t cps, int k,
+// U1b per channel: reduce the channel's `per` partial maxima (they lie together, channel after
+// channel), write s to the header and the reciprocal r to the workspace table.  One wavefront
+// per channel.
+__global__ __launch_bounds__(kWave) void range_finalize_kernel(const float* __restrict__ partials, int64_t per, int k,
                                                                 float* __restrict__ header, float* __restrict__ rtab) {
   const int64_t ch = blockIdx.x;
   float c = 0.0f;
-  const int64_t per = n_rows * cps;
-  for (int64_t j = threadIdx.x; j < per; j += kWave) {
-    const int64_t r = j / cps;
-    const int64_t q = j - r * cps;
-    c = fmaxf(c, partials[(r * C + ch) * cps + q]);
-  }
+  for (int64_t j = threadIdx.x; j < per; j += kWave) c = fmaxf(c, partials[ch * per + j]);
   c = wave_max(c);
   if (threadIdx.x == 0) {
     float s, r;
@@ -400,9 +409,10 @@ template <typename T, int K, int MODE, bool STOCH>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     const T* __restrict__ x, uint32_t* __restrict__ payload32, float* __restrict__ header,
     const float* __restrict__ partials, int npart, const float* __restrict__ rtab, int64_t N, int64_t full_tiles,
-    int64_t rev_tiles, int64_t slow_first_group, int64_t payload_bytes, ChanGeom geom, int64_t m, int64_t seg_len,
-    uint64_t seed) {
+    int64_t rev_tiles, int64_t slow_first_group, int64_t payload_bytes, ChanGeom geom, LocalRanges local, int64_t m,
+    int64_t seg_len, uint64_t seed) {
   constexpr int VEC = Elem<T>::VEC;
+  constexpr int64_t TILE_VECS = kTileElems / VEC;
   constexpr int QPV = VEC / 4;                       // pieces per vector
   constexpr int LOADS = kTileElems / (kBlock * VEC);  // vectors per thread per tile
   constexpr int PIECES = kTileElems / 4;
@@ -410,6 +420,25 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
   __shared__ float red[kBlock / kWave];
 
   const int tid = threadIdx.x;
+  // Tile order.  The range pass has just read the tensor front to back, so its end is what the
+  // caches still hold: the first rev_tiles tiles (a multiple of 8, as is the grid then) are taken
+  // last to first in groups of eight, tile = rev_tiles - 8 - 8*(i / 8) + i % 8 for the i-th tile
+  // of the plain order.  A workgroup's tiles then step backwards by one grid stride, and tile and
+  // workgroup index stay equal modulo 8: the die that read a tile in the range pass reads it
+  // again here.  The up to seven tiles after rev_tiles keep their plain places.
+  auto tile_of = [&](int64_t tile_f) {
+    return tile_f < rev_tiles ? rev_tiles - 8 - (tile_f & ~int64_t(7)) + (tile_f & 7) : tile_f;
+  };
+  // A tile's rows are asked for one tile ahead: those of the first tile here, before anything
+  // else, those of every later tile as soon as the tile before it has been quantized.
+  uint4 raw[LOADS];
+  auto ask_for_tile = [&](int64_t tile) {
+    const T* xt = x + tile * kTileElems;
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) raw[u] = load16_stream(xt + (u * kBlock + tid) * VEC);
+  };
+  if (int64_t(blockIdx.x) < full_tiles) ask_for_tile(tile_of(blockIdx.x));
+
   float r_tensor = 0.0f;
   if (MODE == kOneRange) {
     float c = 0.0f;
@@ -425,36 +454,115 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     if (blockIdx.x == 0 && tid == 0) header[0] = s;
   }
 
-  // Tile order.  The range pass has just read the tensor front to back, so its end is what the
-  // caches still hold: the first rev_tiles tiles (a multiple of 8, as is the grid then) are taken
-  // last to first in groups of eight, tile = rev_tiles - 8 - 8*(i / 8) + i % 8 for the i-th tile
-  // of the plain order.  A workgroup's tiles then step backwards by one grid stride, and tile and
-  // workgroup index stay equal modulo 8: the die that read a tile in the range pass reads it
-  // again here.  The up to seven tiles after rev_tiles keep their plain places.
-  ChanPos tile_pos{0, 0};
+  // Channel position of a tile's first vector (the same in all threads), stepped from tile to
+  // tile; a thread's own position is that plus its index.
+  ChanPos first_pos{0, 0};
+  ChanStep mine{0, 0};
+  if (MODE != kOneRange && int64_t(blockIdx.x) < full_tiles) {
+    first_pos = chan_init(geom, tile_of(blockIdx.x) * TILE_VECS);
+    mine.dr = int64_t(tid) % geom.seg_vecs;
+    mine.dch = int32_t((int64_t(tid) / geom.seg_vecs) % geom.C);
+  }
+
+  // kRangePerVectorLocal: the reciprocals of the channels a tile touches, entry t for channel
+  // (first channel of the tile + t) mod C, t < min(segments the tile touches, C).  Wavefront w
+  // fills the entries w, w+4, ...: the maximum over the channel's `per` partial maxima (at most
+  // two per lane), then U1b; the workgroup whose tile holds the start of the channel's segment
+  // of batch row 0 writes s to the header.  A table is filled one tile ahead (it is double
+  // buffered like the pieces, and the tile's one barrier publishes it): the partial maxima are
+  // asked for before the tile is quantized and looked at after, so that their way from memory
+  // (another die wrote them) is not waited for.
+  constexpr int kLocalPerLane = 2, kLocalPerWave = kLocalRanges / (kBlock / kWave);
+  static_assert(kLocalRanges % (kBlock / kWave) == 0, "entries per wavefront");
+  __shared__ float local_r[2][kLocalRanges];
+  struct LocalFetch {
+    float v[kLocalPerWave][kLocalPerLane];
+  };
+  const int lane = tid & (kWave - 1);
+  // does entry t exist for a tile whose first vector sits `rem` vectors into its segment?
+  auto local_entry = [&](int t, const ChanPos& p0) {
+    return t < geom.C && int64_t(t) * geom.seg_vecs - p0.rem < TILE_VECS;
+  };
+  auto local_fetch = [&](const ChanPos& p0, LocalFetch& lf) {
+#pragma unroll
+    for (int e = 0; e < kLocalPerWave; ++e) {
+      const int t = tid / kWave + e * (kBlock / kWave);
+      int32_t ch = p0.ch + t;
+      if (ch >= geom.C) ch -= geom.C;
+      const bool has = local_entry(t, p0);
+#pragma unroll
+      for (int l = 0; l < kLocalPerLane; ++l) {
+        const int i = lane + l * kWave;
+        lf.v[e][l] = (has && i < local.per) ? partials[uint32_t(ch * local.per + i)] : 0.0f;  // C * per < 2^31 (host)
+      }
+    }
+  };
+  auto local_finish = [&](int64_t tile, const ChanPos& p0, const LocalFetch& lf, float* table) {
+#pragma unroll
+    for (int e = 0; e < kLocalPerWave; ++e) {
+      const int t = tid / kWave + e * (kBlock / kWave);
+      if (!local_entry(t, p0)) break;  // the same in all lanes of the wavefront
+      float c = lf.v[e][0];
+#pragma unroll
+      for (int l = 1; l < kLocalPerLane; ++l) c = fmaxf(c, lf.v[e][l]);
+      c = wave_max(c);
+      if (lane == 0) {
+        float sc, r;
+        scale_from_range(c, K, sc, r);
+        table[t] = r;
+        int32_t ch = p0.ch + t;
+        if (ch >= geom.C) ch -= geom.C;
+        // segment t of the tile starts t*seg_vecs - rem vectors after the tile's first vector:
+        // inside the tile, and in batch row 0?
+        const int64_t start = int64_t(t) * geom.seg_vecs - p0.rem;
+        if (start >= 0 && tile * TILE_VECS + start < int64_t(geom.C) * geom.seg_vecs) header[ch] = sc;
+      }
+    }
+  };
+  if (MODE == kRangePerVectorLocal && int64_t(blockIdx.x) < full_tiles) {
+    LocalFetch lf;
+    local_fetch(first_pos, lf);
+    local_finish(tile_of(blockIdx.x), first_pos, lf, local_r[0]);
+    __syncthreads();
+  }
+
   int buf = 0;
   for (int64_t tile_f = blockIdx.x; tile_f < full_tiles; tile_f += gridDim.x, buf ^= 1) {
-    const bool reversed = tile_f < rev_tiles;
-    const int64_t tile = reversed ? rev_tiles - 8 - (tile_f & ~int64_t(7)) + (tile_f & 7) : tile_f;
-    // the workgroup's first tile, and its one tile (if any) beyond the reversed part
-    if (MODE != kOneRange && (tile_f == int64_t(blockIdx.x) || !reversed))
-      tile_pos = chan_init(geom, tile * (kTileElems / VEC) + tid);
-    const T* xt = x + tile * kTileElems;
-    float f[LOADS][VEC];
-#pragma unroll
-    for (int u = 0; u < LOADS; ++u) load_vec_stream(xt + (u * kBlock + tid) * VEC, f[u]);
-    ChanPos pos = tile_pos;
+    const int64_t tile = tile_of(tile_f);
+    // the next tile of this workgroup: one grid stride back inside the reversed part
+    const int64_t next_f = tile_f + gridDim.x;
+    ChanPos next_pos = first_pos;
+    LocalFetch next_lf;
+    if (MODE != kOneRange && next_f < full_tiles) {
+      if (next_f < rev_tiles) chan_retreat(geom, next_pos, geom.sgrid);
+      else next_pos = chan_init(geom, tile_of(next_f) * TILE_VECS);
+      if (MODE == kRangePerVectorLocal) local_fetch(next_pos, next_lf);
+    }
+    ChanPos pos = first_pos;
+    if (MODE != kOneRange) chan_advance(geom, pos, mine);
+    const int32_t ch0 = first_pos.ch;
 #pragma unroll
     for (int u = 0; u < LOADS; ++u) {
       float r[VEC];
-      ranges_of_vector<MODE, VEC>(rtab, r_tensor, pos.ch, r);
+      if (MODE == kRangePerVectorLocal) {
+        int32_t t = pos.ch - ch0;
+        if (t < 0) t += geom.C;
+        ranges_of_vector<MODE, VEC>(local_r[buf], r_tensor, t, r);
+      } else {
+        ranges_of_vector<MODE, VEC>(rtab, r_tensor, pos.ch, r);
+      }
       if (MODE != kOneRange) chan_advance(geom, pos, geom.s256);
       const int64_t e0 = tile * kTileElems + int64_t(u * kBlock + tid) * VEC;
+      float f[VEC];
+      widen(raw[u], f);
 #pragma unroll
       for (int h = 0; h < QPV; ++h)
-        pieces[buf][(u * kBlock + tid) * QPV + h] = quantize4<K, STOCH>(&f[u][4 * h], &r[4 * h], seed, e0 + 4 * h);
+        pieces[buf][(u * kBlock + tid) * QPV + h] = quantize4<K, STOCH>(&f[4 * h], &r[4 * h], seed, e0 + 4 * h);
     }
-    if (MODE != kOneRange) chan_retreat(geom, tile_pos, geom.sgrid);
+    if (next_f < full_tiles) ask_for_tile(tile_of(next_f));
+    if (MODE == kRangePerVectorLocal && next_f < full_tiles)
+      local_finish(tile_of(next_f), next_pos, next_lf, local_r[buf ^ 1]);
+    first_pos = next_pos;
     __syncthreads();
     const uint4 a = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid]);
     const uint4 b = *reinterpret_cast<const uint4*>(&pieces[buf][8 * tid + 4]);
@@ -659,8 +767,8 @@ hipError_t launch_quant(const accept_desc& d, const UPlan& p, const T* x, float*
   }
   const int64_t payload_bytes = (N * K + 7) / 8;
   hipLaunchKernelGGL((quantize_pack_kernel<T, K, MODE, STOCH>), dim3(grid), dim3(kBlock), 0, s, x, payload, header,
-                     partials, p.range_grid, rtab, N, full_tiles, rev_tiles, slow_first, payload_bytes, g, p.m,
-                     p.seg_len, d.seed);
+                     partials, p.range_grid, rtab, N, full_tiles, rev_tiles, slow_first, payload_bytes, g,
+                     LocalRanges{int32_t(d.n * p.cps)}, p.m, p.seg_len, d.seed);
   return hipGetLastError();
 }
 
@@ -853,6 +961,10 @@ hipError_t launch_quant_k(const accept_desc& d, const UPlan& p, const T* x, floa
     return stoch ? launch_quant<T, K, kRangePerElement, true>(d, p, x, header, payload, partials, rtab, s)
                  : launch_quant<T, K, kRangePerElement, false>(d, p, x, header, payload, partials, rtab, s);
   }
+  if (p.local_ranges) {
+    return stoch ? launch_quant<T, K, kRangePerVectorLocal, true>(d, p, x, header, payload, partials, rtab, s)
+                 : launch_quant<T, K, kRangePerVectorLocal, false>(d, p, x, header, payload, partials, rtab, s);
+  }
   return stoch ? launch_quant<T, K, kRangePerVector, true>(d, p, x, header, payload, partials, rtab, s)
                : launch_quant<T, K, kRangePerVector, false>(d, p, x, header, payload, partials, rtab, s);
 }
@@ -868,7 +980,7 @@ hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, floa
   } else if (p.mode == U_SEGMENTED) {
     const int64_t tiles = (p.N + kTileElems - 1) / kTileElems;  // below 2^31: N is at most 2^40
     hipLaunchKernelGGL((range_segments_kernel<T>), dim3(unsigned(tiles)), dim3(kBlock), 0, s, x, p.items, p.cps,
-                       p.seg_len / p.vec, p.chunk_vecs, partials);
+                       p.seg_len / p.vec, p.chunk_vecs, d.n, p.C, partials);
   } else {
     const dim3 grid(unsigned(p.col_grid_x), unsigned(p.col_grid_y));
     if (p.m % Elem<T>::VEC == 0)
@@ -887,12 +999,12 @@ hipError_t compress_typed(const accept_desc& d, const UPlan& p, const T* x, floa
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     mark(tm, s);
-  } else if (p.mode != U_TENSOR || plain) {
+  } else if ((p.mode != U_TENSOR || plain) && !(p.local_ranges && !plain)) {
     // the per-tensor pass leaves range_grid maxima: one row, one channel, range_grid chunks
     const int64_t rows = p.mode == U_SEGMENTED ? d.n : 1;
     const int64_t cps = p.mode == U_SEGMENTED ? p.cps : p.range_grid;
-    hipLaunchKernelGGL(range_finalize_kernel, dim3(unsigned(p.C)), dim3(kWave), 0, s, partials, rows, p.C, cps,
-                       d.bits, header, rtab);
+    hipLaunchKernelGGL(range_finalize_kernel, dim3(unsigned(p.C)), dim3(kWave), 0, s, partials, rows * cps, d.bits,
+                       header, rtab);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     mark(tm, s);
@@ -1039,6 +1151,10 @@ UPlan make_uplan(const accept_desc& d) {
     p.chunk_vecs = (seg_vecs + p.cps - 1) / p.cps;
     p.items = d.n * p.C * p.cps;
     partial_bytes = size_t(p.items) * sizeof(float);
+    // A tensor of whole tiles with few partial maxima per channel: the quantize pass finishes the
+    // ranges of each tile's channels itself (no U1b kernel between the passes).
+    p.local_ranges = p.N % kTileElems == 0 && p.seg_len >= kLocalMinSegment && d.n * p.cps <= 128 &&
+                     p.C * d.n * p.cps < (int64_t(1) << 31) && d.layout == ACCEPT_LAYOUT_PACKED;
   } else {
     p.mode = U_GENERIC;
     // channels-last (one element per segment) with rows of whole vectors: the quantizer's fast

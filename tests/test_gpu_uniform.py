@@ -124,6 +124,28 @@ def test_per_channel_segmented(A, k, in_bf16):
     run_case(A, x, k, 2, 60000, channels=3, in_bf16=in_bf16, tag="seg20000")
 
 
+@pytest.mark.parametrize("k", [2, 5, 8])
+def test_per_channel_whole_tiles(A, k):
+    """Tensors of whole 8192-element tiles with long segments: the quantize pass finishes the
+    channels' ranges itself, tile by tile.  Tiles that touch more segments than there are
+    channels, one segment over several tiles (two chunks per segment), many rows (several
+    partial maxima per lane), float32 and bfloat16, and the same shapes one row short of whole
+    tiles (separate U1b kernel) for comparison."""
+    for n, C, seg in [(16, 3, 512), (4, 16, 512), (8, 40, 1024), (2, 5, 8192), (4, 2, 16384), (300, 4, 2048),
+                      (64, 3, 1536), (1024, 1, 512)]:
+        if C == 1:
+            continue  # one channel is the per-tensor mode
+        x = si.make_shape("relu_lognormal_chgain", (n, C, seg), 80 + k)
+        gain = np.float32(10.0) ** np.linspace(-2, 2, C, dtype=np.float32)
+        x = np.ascontiguousarray(x * gain[None, :, None], dtype=np.float32)
+        assert (n * C * seg) % 8192 == 0
+        run_case(A, x, k, n, C * seg, channels=C, tag="whole tiles seg%d C%d" % (seg, C))
+        run_case(A, x, k, n, C * seg, channels=C, in_bf16=True, out_bf16=True, tag="whole tiles bf16")
+        run_case(A, x[: n - 1], k, n - 1, C * seg, channels=C, tag="one row short") if (n - 1) * C * seg % 8192 else None
+    x = si.make_shape("grad_outliers", (8, 4, 2048), 90 + k)
+    run_case(A, x, k, 8, 8192, channels=4, rounding=1, seed=5, tag="whole tiles stochastic")
+
+
 @pytest.mark.parametrize("k", [3, 4, 8])
 def test_per_channel_generic_geometries(A, k):
     # short aligned segments (vector quantize path, column range pass)
