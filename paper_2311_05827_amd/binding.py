@@ -46,6 +46,10 @@ def _load():
         raise ImportError(
             "libaccept.so is not built (%s). Run `python -m paper_2311_05827_amd.build`; "
             "there is no CPU fallback." % LIB_PATH)
+    # PyTorch first: it brings its own copy of the HIP runtime, and the library and PyTorch must
+    # share one (they exchange stream handles and device pointers).  The dynamic loader gives
+    # the library whichever copy is already in the process, so the order of the two loads decides.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     P, V, I = ctypes.POINTER, ctypes.c_void_p, ctypes.c_int
     sz = P(ctypes.c_size_t)
