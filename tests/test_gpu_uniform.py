@@ -146,6 +146,30 @@ def test_per_channel_whole_tiles(A, k):
     run_case(A, x, k, 8, 8192, channels=4, rounding=1, seed=5, tag="whole tiles stochastic")
 
 
+@pytest.mark.parametrize("k", [3, 8])
+def test_more_tiles_than_workgroups(A, k):
+    """Tensors of more than 2048 tiles: workgroups take several tiles each, last-read first, and
+    step their channel position backwards; a few tiles after the last whole group of eight keep
+    their plain places.  One range, one range per channel (with and without whole tiles) and
+    one range per element."""
+    T = 8192
+    # one range: 2051 whole tiles (3 after the reversed part) and a ragged tail
+    x = si.make_shape("grad_outliers", (1, 2051 * T + 77), 95 + k)
+    run_case(A, x, k, 1, 2051 * T + 77, tag="2051 tiles + tail")
+    # one range per channel, whole tiles (ranges finished tile by tile): 64 x 5 x 53248 = 2080 tiles
+    x = si.make_shape("relu_lognormal_chgain", (64, 5, 53248), 96 + k)
+    run_case(A, x, k, 64, 5 * 53248, channels=5, tag="2080 tiles per channel")
+    run_case(A, x, k, 64, 5 * 53248, channels=5, in_bf16=True, out_bf16=True, tag="1040 tiles per channel bf16")
+    # the same one segment length off whole tiles (range table from the U1b kernel, ragged tail)
+    x = si.make_shape("relu_lognormal_chgain", (64, 5, 53256), 97 + k)
+    run_case(A, x, k, 64, 5 * 53256, channels=5, tag="2080 tiles + tail per channel")
+    # channels-last: 266240 rows of 64 channels = 2080 tiles, and 5 rows more
+    x = si.make_shape("grad", (266245, 64), 98 + k) * (np.arange(1, 65, dtype=np.float32)[None, :])
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    run_case(A, x[:266240], k, 266240, 64, channels=64, tag="2080 tiles channels-last")
+    run_case(A, x, k, 266245, 64, channels=64, tag="2080 tiles channels-last + tail")
+
+
 @pytest.mark.parametrize("k", [3, 4, 8])
 def test_per_channel_generic_geometries(A, k):
     # short aligned segments (vector quantize path, column range pass)
