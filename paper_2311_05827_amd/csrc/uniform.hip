@@ -194,21 +194,24 @@ __global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restr
     if (count > chunk_vecs) count = chunk_vecs;
     const T* base = x + (sid * seg_vecs + first) * VEC;
     float c = 0.0f;
-    int64_t j = lane;
-    for (; j + 3 * kWave < count; j += 4 * kWave) {
-      float f[4][VEC];
+    // eight loads in flight per lane, kept as raw vectors until used; a lane whose turn lies
+    // beyond the chunk's end re-reads the chunk's last vector (a maximum does not mind), so that
+    // the loads stay unconditional and a chunk's last vectors do not cost a trip to memory each
+    for (int64_t j = lane; j < count; j += 8 * kWave) {
+      uint4 raw[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) load_range<T, VEC>(base + (j + u * kWave) * VEC, f[u]);
+      for (int u = 0; u < 8; ++u) {
+        int64_t idx = j + u * kWave;
+        if (idx >= count) idx = count - 1;
+        raw[u] = load16(base + idx * VEC);
+      }
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 8; ++u) {
+        float f[VEC];
+        widen(raw[u], f);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[u][e]));
-    }
-    for (; j < count; j += kWave) {
-      float f[VEC];
-      load_range<T, VEC>(base + j * VEC, f);
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[e]));
+        for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[e]));
+      }
     }
     c = wave_max(c);  // every lane of the wavefront reaches this point: the loop bounds are wave-uniform
     const int64_t row = sid / C;
