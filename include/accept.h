@@ -132,13 +132,13 @@ accept_status accept_workspace_size(const accept_desc* desc, size_t* bytes);
  *     residue initialisation).  One pass assigns every element to its nearest level,
  *     writes the bit planes (byte ((g*m + j)*k + p), g = row/8, holds bit p of rows
  *     8g..8g+7 of column j, first row in the most significant bit, rows >= n as 0) and
- *     accumulates the least-squares sums; the workgroup that finishes last solves for
- *     alpha_t and writes header = [alpha_t, m_q] (one kernel in all).  Feed header[0..k)
- *     back as alpha_prev of the next batch.
+ *     accumulates the least-squares sums; a second, small kernel solves for alpha_t
+ *     (eqs. (alpha solution), (alpha update)) and writes header = [alpha_t, m_q].  Feed
+ *     header[0..k) back as alpha_prev of the next batch.
  *
  * workspace_dev: accept_workspace_size bytes, 256-byte aligned.  Zero-fill it once after
  * allocating it (hipMemset); from then on the library keeps it in the state its next call
- * needs (its first 256 bytes hold counters that every kernel leaves at zero; the rest is
+ * needs (its first 16 KiB hold counters that every call leaves at zero; the rest is
  * scratch whose contents do not matter), so one workspace serves any number of calls and
  * descriptors of both schemes, one call at a time: calls that share a workspace must not
  * overlap.

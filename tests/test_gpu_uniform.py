@@ -160,6 +160,11 @@ def test_more_tiles_than_workgroups(A, k):
     x = si.make_shape("relu_lognormal_chgain", (64, 5, 53248), 96 + k)
     run_case(A, x, k, 64, 5 * 53248, channels=5, tag="2080 tiles per channel")
     run_case(A, x, k, 64, 5 * 53248, channels=5, in_bf16=True, out_bf16=True, tag="1040 tiles per channel bf16")
+    # few rows, so few partial maxima per channel: the quantize pass finishes the ranges itself,
+    # also for the workgroups that take two tiles (16 x 160 x 6656 = 2080 tiles of 2-3 segments)
+    x = si.make_shape("relu_lognormal_chgain", (16, 160, 6656), 99 + k)
+    run_case(A, x, k, 16, 160 * 6656, channels=160, tag="2080 tiles, ranges per tile")
+    run_case(A, x, k, 16, 160 * 6656, channels=160, in_bf16=True, out_bf16=True, tag="1040 tiles bf16, ranges per tile")
     # the same one segment length off whole tiles (range table from the U1b kernel, ragged tail)
     x = si.make_shape("relu_lognormal_chgain", (64, 5, 53256), 97 + k)
     run_case(A, x, k, 64, 5 * 53256, channels=5, tag="2080 tiles + tail per channel")
