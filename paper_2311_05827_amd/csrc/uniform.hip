@@ -406,8 +406,12 @@ __device__ __forceinline__ void quantize_group8(const T* __restrict__ x, uint8_t
 // every thread loads 16-byte vectors (contiguous across lanes), quantizes them into pieces,
 // parks the pieces in LDS; after one barrier thread g reads pieces 8g..8g+7 (32 consecutive
 // elements) and emits k contiguous dwords.  The piece buffer is double buffered so that one
-// barrier per tile is enough.  Per-tensor mode folds U1b into the prologue: every workgroup
-// reduces the range pass's partial maxima itself and workgroup 0 writes s to the header.
+// barrier per tile is enough.  MODE says where an element's range comes from (kOneRange ..
+// kRangePerVectorLocal above).  kOneRange folds U1b into the prologue: every workgroup reduces
+// the range pass's partial maxima itself and workgroup 0 writes s to the header;
+// kRangePerVectorLocal folds it into the tile loop (see local_r below); the other two modes read
+// the table that a U1b kernel has written.  Elements after the last whole tile take the slow
+// path at the end.
 template <typename T, int K, int MODE, bool STOCH>
 __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
     const T* __restrict__ x, uint32_t* __restrict__ payload32, float* __restrict__ header,
@@ -432,7 +436,7 @@ __global__ __launch_bounds__(kBlock) void quantize_pack_kernel(
   auto tile_of = [&](int64_t tile_f) {
     return tile_f < rev_tiles ? rev_tiles - 8 - (tile_f & ~int64_t(7)) + (tile_f & 7) : tile_f;
   };
-  // A tile's rows are asked for one tile ahead: those of the first tile here, before anything
+  // A tile's vectors are asked for one tile ahead: those of the first tile here, before anything
   // else, those of every later tile as soon as the tile before it has been quantized.
   uint4 raw[LOADS];
   auto ask_for_tile = [&](int64_t tile) {
