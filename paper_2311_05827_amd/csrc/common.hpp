@@ -135,6 +135,29 @@ __device__ __forceinline__ void store_dwords(uint32_t* p, const uint32_t (&v)[ND
   *reinterpret_cast<Block*>(p) = b;
 }
 
+// The same with streaming stores (the MBQ encoder's planes: fewer dirty lines are left for the
+// end of the kernel, which the finalize kernel's start waits for).
+template <int NDW>
+__device__ __forceinline__ void store_dwords_stream(uint32_t* p, const uint32_t (&v)[NDW]) {
+  if constexpr (NDW % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < NDW; i += 4) {
+      const v4u_t u = {v[i], v[i + 1], v[i + 2], v[i + 3]};
+      __builtin_nontemporal_store(u, reinterpret_cast<v4u_t*>(p + i));
+    }
+  } else if constexpr (NDW % 2 == 0) {
+    typedef uint32_t v2u_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int i = 0; i < NDW; i += 2) {
+      const v2u_t u = {v[i], v[i + 1]};
+      __builtin_nontemporal_store(u, reinterpret_cast<v2u_t*>(p + i));
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < NDW; ++i) __builtin_nontemporal_store(v[i], p + i);
+  }
+}
+
 __device__ __forceinline__ void widen(const uint4 v, float (&f)[4]) {
   f[0] = u32_as_f32(v.x); f[1] = u32_as_f32(v.y); f[2] = u32_as_f32(v.z); f[3] = u32_as_f32(v.w);
 }

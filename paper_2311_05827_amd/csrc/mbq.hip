@@ -407,7 +407,7 @@ __device__ __forceinline__ void finish_item(const uint32_t (&acc)[VEC][(K + 3) /
           out[b / 4] |= ((acc[c][p / 4] >> (8 * (p % 4))) & 0xFFu) << (8 * (b % 4));
         }
     }
-    store_dwords<NDW>(reinterpret_cast<uint32_t*>(dst), out);
+    store_dwords_stream<NDW>(reinterpret_cast<uint32_t*>(dst), out);
   } else {
 #pragma unroll
     for (int p = 0; p < K; ++p) dst[p] = uint8_t(acc[0][p / 4] >> (8 * (p % 4)));
@@ -649,8 +649,8 @@ __device__ __forceinline__ void encode_stream(const EncodeTables<K>& tb, const T
 // lives in registers.  tot: sums of x over the +1 entries of each plane, sum of x, +1 counts
 // per plane, disagreement counts per plane pair.
 template <int K>
-__device__ __forceinline__ void solve_and_write_header(const double* tot, const float* __restrict__ alpha_prev,
-                                                       double n_elems, double t, float* __restrict__ header) {
+__device__ __forceinline__ void solve_and_write_header(const double* tot, const float (&alpha_prev)[K], double n_elems,
+                                                       double beta, float* __restrict__ header) {
   double G[K][K], b[K], Sb[K], a_prev[K], cur[K];
   const double Sx = tot[K];
   {
@@ -701,8 +701,6 @@ __device__ __forceinline__ void solve_and_write_header(const double* tot, const 
     for (int c = r + 1; c < K; ++c) acc -= G[r][c] * cur[c];
     cur[r] = singular ? a_prev[r] : acc * inv[r];
   }
-  double beta = (1.0 + t) / (10.0 + t);
-  if (beta > 0.9) beta = 0.9;
   double dot = 0.0;
 #pragma unroll
   for (int p = 0; p < K; ++p) {
@@ -721,7 +719,8 @@ struct MbqCall {
   double* records;
   const float* alpha_prev;
   float* header;
-  double n_elems, t;
+  double n_elems;
+  double beta;  // weight of the previous coefficients in the moving average: min(0.9, (1+t)/(10+t))
 };
 
 // End of an encode kernel (M4): the workgroup adds up its threads' statistics in a fixed order
@@ -751,6 +750,9 @@ __global__ __launch_bounds__(kBlock) void mbq_finalize_kernel(MbqCall call, int 
   __shared__ WaveTotals red;
   __shared__ double tot[48];
   const int tid = threadIdx.x;
+  float alpha_prev[K];  // asked for together with the records: the solve at the end would otherwise wait for them
+#pragma unroll
+  for (int p = 0; p < K; ++p) alpha_prev[p] = call.alpha_prev[p];
   double a[NSTAT];
 #pragma unroll
   for (int s = 0; s < NSTAT; ++s) a[s] = 0.0;
@@ -765,7 +767,7 @@ __global__ __launch_bounds__(kBlock) void mbq_finalize_kernel(MbqCall call, int 
   if (tid < NSTAT) tot[tid] = total;
   if (tid < kMaxGroups) call.counters[tid * kCounterStride] = 0u;  // the encode kernel's work counters, for the next call
   __syncthreads();
-  if (tid == 0) solve_and_write_header<K>(tot, call.alpha_prev, call.n_elems, call.t, call.header);
+  if (tid == 0) solve_and_write_header<K>(tot, alpha_prev, call.n_elems, call.beta, call.header);
 }
 
 // Fused M1..M4.  Complete row groups go through the pipelined stream: row r of the next
@@ -1264,7 +1266,8 @@ MbqCall make_call(const accept_desc& d, const float* alpha_prev, void* header, v
   c.alpha_prev = alpha_prev;
   c.header = static_cast<float*>(header);
   c.n_elems = double(d.n) * double(d.m);
-  c.t = double(d.t);
+  const double beta = (1.0 + double(d.t)) / (10.0 + double(d.t));  // eq. (alpha update)
+  c.beta = beta > 0.9 ? 0.9 : beta;
   return c;
 }
 
