@@ -56,6 +56,54 @@ def test_uniform_random_geometries(A):
         assert out_to_numpy(xh).tobytes() == ref.tobytes(), case
 
 
+def test_uniform_random_tiled_geometries(A):
+    """Per-channel geometries over several 8192-element tiles, drawn so that every way of
+    finding an element's range is hit: long segments with the ranges finished tile by tile
+    (whole tiles, few rows) or by the U1b kernel, short aligned segments, unaligned segments,
+    one element per segment (channels-last)."""
+    torch = torch_mod()
+    rng = np.random.default_rng(20231107)
+    for case in range(72):
+        flavour = case % 6
+        if flavour == 0:      # whole tiles, segments >= 2048: ranges per tile
+            seg = 2048 * int(rng.integers(1, 6)) + 512 * int(rng.integers(0, 4)) * (case % 12 == 0)
+            C = int(rng.integers(2, 9))
+            n = 8192 // np.gcd(8192, C * seg) * int(rng.integers(1, 4))
+        elif flavour == 1:    # long segments, not whole tiles
+            seg = 4 * int(rng.integers(128, 2000))
+            C, n = int(rng.integers(2, 7)), int(rng.integers(1, 9))
+        elif flavour == 2:    # short aligned segments
+            seg = 8 * int(rng.integers(1, 60))
+            C, n = int(rng.integers(2, 40)), int(rng.integers(8, 60))
+        elif flavour == 3:    # segments no vector respects
+            seg = int(rng.integers(1, 50)) * 2 + 1
+            C, n = int(rng.integers(2, 40)), int(rng.integers(8, 80))
+        elif flavour == 4:    # channels-last, rows of whole vectors
+            seg, C, n = 1, 8 * int(rng.integers(1, 40)), int(rng.integers(30, 900))
+        else:                 # channels-last, rows that no vector divides
+            seg, C, n = 1, int(rng.integers(3, 200)) | 1, int(rng.integers(30, 500))
+        n, C, seg = int(n), int(C), int(seg)
+        m = C * seg
+        k = int(rng.integers(2, 9))
+        bf = bool(rng.integers(0, 2))
+        rounding = 1 if case % 9 == 0 else 0
+        x = si.make_shape("relu_lognormal_chgain" if seg > 1 else "grad", (n, C, seg) if seg > 1 else (n, C), 8000 + case)
+        if seg == 1:
+            x = np.ascontiguousarray(x * (np.float32(2.0) ** rng.integers(-8, 8, C).astype(np.float32))[None, :], np.float32)
+        print("case", case, "n", n, "C", C, "seg", seg, "k", k, "bf16", bf, "rnd", rounding, "N", n * m, flush=True)
+        xd, bits = to_dev(x, bf)
+        d = A.make_desc(A.UNIFORM, k, n, m, channels=C, in_dtype=A.BF16 if bf else A.F32,
+                        out_dtype=A.BF16 if bf else A.F32, rounding=rounding, seed=case)
+        header, payload = A.accept_compress(d, xd)
+        xh = A.accept_decompress(d, header, payload)
+        torch.cuda.synchronize()
+        oh, op = orc.uniform_compress(bits if bf else x, k, n, m, C, bf, rounding, case)
+        assert dev_bytes(header) == oh, case
+        mm = first_mismatch(dev_bytes(payload), op.tobytes())
+        assert mm is None, (case, mm)
+        assert out_to_numpy(xh).tobytes() == orc.uniform_decompress(oh, op, k, n, m, C, bf).tobytes(), case
+
+
 def test_mbq_random_geometries(A):
     torch = torch_mod()
     rng = np.random.default_rng(20231106)
