@@ -14,9 +14,14 @@ namespace accept {
 
 namespace {
 
-// The range pass reads with ordinary (cacheable) loads: the quantize pass reads the same tensor
-// again right after it, last-read data first, and finds a good part of it still in the memory-side
-// cache and the end of it in L2 (streaming loads would leave neither).
+// The range pass reads the end of the tensor with ordinary (cacheable) loads: the quantize pass
+// reads the same tensor again right after it, last-read data first, and finds that part still
+// in the memory-side cache (streaming loads would leave nothing there).  What lies more than
+// kRangeKeepBytes before the end is read with streaming loads: little of it would survive until
+// the quantize pass gets there, cacheable loads are the slower kind, most of all behind a kernel
+// whose stores are still draining, and whatever they bring into the memory-side cache pushes
+// out what other kernels left there (the payload a decoder is about to read, for one).
+constexpr int64_t kRangeKeepBytes = int64_t(96) << 20;  // of the 256 MiB memory-side cache
 template <typename T, int V>
 __device__ __forceinline__ void load_range(const T* p, float (&f)[V]) {
   widen(load16(p), f);
@@ -133,7 +138,20 @@ __global__ __launch_bounds__(kBlock) void range_tensor_kernel(const T* __restric
   const int64_t nvec = N / VEC;
   const int64_t full_tiles = N / kTileElems;
   float c = 0.0f;
-  for (int64_t tile = blockIdx.x; tile < full_tiles; tile += gridDim.x) {
+  constexpr int64_t KEEP_TILES = kRangeKeepBytes / int64_t(kTileElems * sizeof(T));
+  const int64_t stream_tiles = full_tiles > KEEP_TILES ? full_tiles - KEEP_TILES : 0;
+  int64_t tile = blockIdx.x;
+  for (; tile < stream_tiles; tile += gridDim.x) {  // streaming loads
+    const T* xt = x + tile * kTileElems;
+    float f[LOADS][VEC];
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u) load_vec_stream(xt + (u * kBlock + threadIdx.x) * VEC, f[u]);
+#pragma unroll
+    for (int u = 0; u < LOADS; ++u)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) c = fmaxf(c, fabsf(f[u][e]));
+  }
+  for (; tile < full_tiles; tile += gridDim.x) {  // cacheable loads
     const T* xt = x + tile * kTileElems;
     float f[LOADS][VEC];
 #pragma unroll
@@ -197,13 +215,26 @@ __global__ __launch_bounds__(kBlock) void range_segments_kernel(const T* __restr
     // eight loads in flight per lane, kept as raw vectors until used; a lane whose turn lies
     // beyond the chunk's end re-reads the chunk's last vector (a maximum does not mind), so that
     // the loads stay unconditional and a chunk's last vectors do not cost a trip to memory each
+    // (a chunk that begins in the part of the tensor that is read with streaming loads: see
+    // kRangeKeepBytes; the choice is the same for all lanes of the wavefront)
+    const bool stream = (sid * seg_vecs + first) * int64_t(VEC * sizeof(T)) + kRangeKeepBytes <
+                        items / cps * seg_vecs * int64_t(VEC * sizeof(T));
     for (int64_t j = lane; j < count; j += 8 * kWave) {
       uint4 raw[8];
+      if (stream) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        int64_t idx = j + u * kWave;
-        if (idx >= count) idx = count - 1;
-        raw[u] = load16(base + idx * VEC);
+        for (int u = 0; u < 8; ++u) {
+          int64_t idx = j + u * kWave;
+          if (idx >= count) idx = count - 1;
+          raw[u] = load16_stream(base + idx * VEC);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          int64_t idx = j + u * kWave;
+          if (idx >= count) idx = count - 1;
+          raw[u] = load16(base + idx * VEC);
+        }
       }
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
