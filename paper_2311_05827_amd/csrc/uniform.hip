@@ -21,7 +21,7 @@ namespace {
 // the quantize pass gets there, cacheable loads are the slower kind, most of all behind a kernel
 // whose stores are still draining, and whatever they bring into the memory-side cache pushes
 // out what other kernels left there (the payload a decoder is about to read, for one).
-constexpr int64_t kRangeKeepBytes = int64_t(96) << 20;  // of the 256 MiB memory-side cache
+constexpr int64_t kRangeKeepBytes = int64_t(64) << 20;  // a quarter of the 256 MiB memory-side cache
 template <typename T, int V>
 __device__ __forceinline__ void load_range(const T* p, float (&f)[V]) {
   widen(load16(p), f);
