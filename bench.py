@@ -18,7 +18,8 @@ tensor and per channel, 4/6/8 bits, fp32 and bf16, the gradient tensor, the forw
 2/3/4) as single calls: cold median and minimum, warm (back-to-back) median, and the
 algorithmic fraction of the HBM peak; "cpu_baseline" is the CPU oracle timed on the same
 workload (one thread, as it stands), "cpu_baseline_all_cores" the same oracle functions run on
-row chunks by a pool of processes.
+row chunks by a pool of processes; with --sweep, "cpu_cells" times the oracle (one thread, best
+of three) on the small configurations as well.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--sweep]
 """
@@ -333,6 +334,7 @@ def main():
         cpu_all = cpu_baseline_all_cores(np, act_np, grad_np, n, m)
 
     cells = [] if args.no_cells else run_cells(A, torch, si, ALL_CELLS if args.sweep else CFG4_CELLS)
+    cpu_small = cpu_cells(np, si) if args.sweep and not args.no_cpu else None
     if args.sweep_json:
         with open(args.sweep_json, "w") as f:
             json.dump(cells, f, indent=1)
@@ -365,6 +367,7 @@ def main():
         "cells": cells,
         "cpu_baseline": cpu,
         "cpu_baseline_all_cores": cpu_all,
+        "cpu_cells": cpu_small,
     }
     print(json.dumps(out), flush=True)
 
@@ -488,6 +491,38 @@ def cpu_baseline(np, act_np, grad_np, n, m):
                   "calls, NumPy oracle, single thread" % (rows, rows * m),
         "seconds": round(dt, 3),
     }
+
+
+def cpu_cells(np, si):
+    """The oracle, single thread, best of three, on the small configurations (1, 2, 5) and one
+    width of configuration 3: seconds per compress and per decompress call, and GB/s of input."""
+    from oracle import accept_oracle as orc
+    plans = [("cfg1_act", "U", 8), ("cfg1_act", "M", 2), ("cfg1_act", "M", 4), ("cfg2_grad", "U", 4),
+             ("cfg2_grad", "U", 2), ("cfg5_hidden", "U", 3), ("cfg5_hidden", "U", 7), ("cfg5_hidden", "M", 3),
+             ("cfg5_grad", "U", 5), ("cfg3_act", "U", 4), ("cfg3_act", "M", 3)]
+    out = []
+    log("%-12s %-2s %1s | %10s %10s | %9s %9s" % ("config", "S", "k", "comp_ms", "dec_ms", "comp_GB/s", "dec_GB/s"))
+    for name, scheme, k in plans:
+        x = si.make(name)
+        n, m = si.as_nm(x)
+        if scheme == "U":
+            comp = lambda: orc.uniform_compress(x, k, n, m)
+            deco = lambda hp: orc.uniform_decompress(hp[0], hp[1], k, n, m)
+        else:
+            alpha, _ = orc.mbq_residue_init(x, k)
+            comp = lambda: orc.mbq_compress(x, k, n, m, alpha, 1)
+            deco = lambda hp: orc.mbq_decompress(hp[0], hp[1], k, n, m)
+        tc = td = 1e30
+        for _ in range(3):
+            t0 = time.perf_counter(); hp = comp(); tc = min(tc, time.perf_counter() - t0)
+            t0 = time.perf_counter(); deco(hp); td = min(td, time.perf_counter() - t0)
+        nb = n * m * 4
+        c = dict(config=name, scheme=scheme, k=k, cores=1, compress_s=round(tc, 5), decompress_s=round(td, 5),
+                 compress_in_GBps=round(nb / tc / 1e9, 4), decompress_out_GBps=round(nb / td / 1e9, 4))
+        out.append(c)
+        log("%-12s %-2s %1d | %10.2f %10.2f | %9.3f %9.3f" % (name, scheme, k, tc * 1e3, td * 1e3,
+                                                           c["compress_in_GBps"], c["decompress_out_GBps"]))
+    return out
 
 
 class CellTimer:
