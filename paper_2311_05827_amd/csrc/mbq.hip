@@ -1364,7 +1364,7 @@ MPlan make_mplan(const accept_desc& d) {
   p.wpg = p.stream ? uint32_t(wpg) : 1u;
   p.n_wave_items = p.stream ? uint32_t(wave_items) : 0u;
   {
-    // one workgroup of 12 wavefronts per compute unit at most; fewer when there is less work
+    // one workgroup of 8 wavefronts per compute unit at most; fewer when there is less work
     int64_t blocks = p.stream ? (wave_items + kEncWaves - 1) / kEncWaves
                               : (full_groups * d.m + kEncBlock - 1) / kEncBlock;
     const int64_t tail_blocks = (d.n % 8 != 0) ? (d.m + kEncBlock - 1) / kEncBlock : 0;
